@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the cacheless MoE decode layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload (default): the single Mixtral-shaped MoE layer in bf16 with all 8 experts
+resident in HBM, batch-1 decode of 256 synthetic tokens, one token at a time.  One
+"step" = the 256 tokens of that batch, each through router GEMV -> top-2 gate -> w1/w3
+GEMV + SiLU -> w2 GEMV + weighted combine.  `value` = tokens/s with weights and
+activations already in HBM when the timed region starts.
+
+Also reported on the same JSON line:
+  roofline      the dominant kernel (w1/w3 GEMV + SiLU) against the HBM peak, timed with
+                HIP events on the compute stream in a second pass over the same steps
+  cacheless     a short run of the 32-layer cacheless stack (experts in pinned host memory,
+                4 HBM slots): H2D expert-load GB/s, tokens/s, step / max(compute, load)
+  cpu_baseline  the float64 NumPy oracle on a bounded sample of the same tokens
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+PCIE5_X16_GBPS = 64.0           # host link, raw per direction
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--tokens", type=int, default=None, help="tokens per step (default: the workload's 256)")
+    ap.add_argument("--cacheless-tokens", type=int, default=3,
+                    help="tokens of the 32-layer cacheless stack to time (0 = skip)")
+    ap.add_argument("--cpu-tokens", type=int, default=3, help="tokens the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+            f"--gpus {args.gpus} is not supported.")
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2512_03927_amd import binding as B
+    from paper_2512_03927_amd import harness, synth
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 3
+    B.lib()  # fails loudly if the HIP library is not built
+
+    cfg = synth.CONFIGS[2]
+    T = args.tokens or cfg.n_tokens
+    t0 = time.time()
+    layer = synth.layer_weights(cfg, 0)
+    X_np = synth.tokens(cfg, T)
+    log(f"[bench] generated {cfg.name}: 8 experts x {cfg.expert_bytes / 1e6:.1f} MB in {time.time() - t0:.1f} s")
+
+    stack = harness.MoEStack(cfg, [layer])
+    X = harness.to_device(X_np)
+    Y = torch.empty_like(X)
+    h = stack.handle
+
+    def step():
+        for t in range(T):
+            B.odmoe_decode_step(h, X[t], Y[t], None, None, None)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens_per_s = T * args.steps / elapsed
+    log(f"[bench] {args.steps} steps x {T} tokens: {ms_per_step:.3f} ms/step, {tokens_per_s:.1f} tokens/s")
+
+    # ---- second pass over the same steps with HIP events around each kernel (compute stream)
+    up_bytes = cfg.top_k * 2 * cfg.hidden * cfg.ffn * 2      # w1 + w3 of the k experts, bf16
+    down_bytes = cfg.top_k * cfg.hidden * cfg.ffn * 2        # w2 of the k experts
+    roofline = None
+    gemv_gbps = None
+    if not args.no_kernel_pass:
+        st = B.odmoe_stats()
+        t_up = t_down = t_route = 0.0
+        n = 0
+        for _ in range(max(1, min(args.steps, 3))):
+            for t in range(T):
+                st.t_step_ms = -1.0
+                B.odmoe_decode_step(h, X[t], Y[t], None, None, st)
+                t_up += st.t_ffn_up_ms
+                t_down += st.t_ffn_down_ms
+                t_route += st.t_route_ms
+                n += 1
+        up_ms, down_ms, route_ms = t_up / n, t_down / n, t_route / n
+        achieved = up_bytes / (up_ms * 1e-3) / 1e9
+        gemv_gbps = (up_bytes + down_bytes) / ((up_ms + down_ms) * 1e-3) / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.json")
+        if os.path.exists(tpath):
+            traffic = json.load(open(tpath)).get("ffn_up_kernel_bytes_per_launch")
+        roofline = {"bound": "hbm", "kernel": "ffn_up_kernel<bf16> (w1/w3 GEMV + SiLU)",
+                    "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                    "algorithmic_bytes_per_launch": up_bytes, "avg_launch_us": round(up_ms * 1e3, 2),
+                    "ffn_down_us": round(down_ms * 1e3, 2), "route_us": round(route_ms * 1e3, 2),
+                    "ffn_down_GBps": round(down_bytes / (down_ms * 1e-3) / 1e9, 1)}
+        log(f"[bench] kernels: up {up_ms * 1e3:.1f} us ({achieved:.0f} GB/s), down {down_ms * 1e3:.1f} us, "
+            f"route {route_ms * 1e3:.1f} us")
+    Y_keep = harness.from_device(Y[:4]).copy()
+    stack.close()
+
+    # ---- cacheless 32-layer stack, short run (host-link roofline)
+    cacheless = None
+    if args.cacheless_tokens > 0:
+        c3 = synth.CONFIGS[3]
+        t0 = time.time()
+        # one unique layer's experts in pinned memory, every layer aliases it: same bytes per token
+        st3 = harness.MoEStack(c3, [layer], unique_layers=1)
+        log(f"[bench] pinned arena ready in {time.time() - t0:.1f} s")
+        x3 = harness.to_device(X_np[0])
+        y3 = torch.empty_like(x3)
+        s = B.odmoe_stats()
+        B.odmoe_decode_step(st3.handle, x3, y3, None, None, s)         # warm-up token
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        loads = 0
+        for t in range(args.cacheless_tokens):
+            B.odmoe_decode_step(st3.handle, harness.to_device(X_np[t % T]), y3, None, None, s)
+            loads += s.loads
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t_start
+        s.t_step_ms = -1.0
+        B.odmoe_decode_step(st3.handle, x3, y3, None, None, s)         # one timed token for the breakdown
+        load_ms = s.t_load_ms
+        comp_ms = s.t_ffn_up_ms + s.t_ffn_down_ms + s.t_glue_ms
+        step_ms = el / args.cacheless_tokens * 1e3
+        h2d = loads * c3.expert_bytes / el / 1e9
+        cacheless = {"workload": c3.name, "tokens": args.cacheless_tokens, "unique_layers": 1,
+                     "tokens_per_s": round(args.cacheless_tokens / el, 4), "ms_per_token": round(step_ms, 2),
+                     "h2d_GBps": round(h2d, 2), "h2d_frac_of_pcie5_x16": round(h2d / PCIE5_X16_GBPS, 4),
+                     "copy_only_ms_per_token": round(load_ms, 2), "kernel_ms_per_token": round(comp_ms, 3),
+                     "step_over_max_compute_load": round(step_ms / max(load_ms, comp_ms), 4),
+                     "hbm_slot_bytes": B.odmoe_slot_pool_bytes(st3.handle)}
+        log(f"[bench] cacheless: {cacheless}")
+        st3.close()
+
+    # ---- CPU oracle on a bounded sample of the same workload
+    cpu = None
+    if args.cpu_tokens > 0:
+        from oracle import moe_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        Wg, b, experts = layer
+        t_start = time.perf_counter()
+        worst = 0.0
+        for t in range(args.cpu_tokens):
+            y_ref, _, _ = O.moe_layer(X_np[t], Wg, b, experts, cfg.top_k)
+            if t < Y_keep.shape[0]:
+                worst = max(worst, float(np.max(np.abs(O.widen(Y_keep[t]) - y_ref)) / np.max(np.abs(y_ref))))
+        el = time.perf_counter() - t_start
+        cpu = {"value": round(args.cpu_tokens / el, 4), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {args.cpu_tokens} of the {T} tokens of {cfg.name} (float64 NumPy oracle)",
+               "gpu_vs_oracle_max_rel_err": worst}
+        log(f"[bench] cpu oracle: {cpu}")
+
+    out = {
+        "metric": "decode tokens/s per MoE layer stack", "value": round(tokens_per_s, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "hidden": cfg.hidden, "ffn": cfg.ffn, "n_experts": cfg.n_experts,
+                   "top_k": cfg.top_k, "n_layers": 1, "tokens_per_step": T, "batch": 1,
+                   "weights": "resident in HBM"},
+        "expert_gemv_hbm_GBps": None if gemv_gbps is None else round(gemv_gbps, 1),
+        "roofline": roofline, "cacheless": cacheless, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

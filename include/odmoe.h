@@ -1,0 +1,189 @@
+/*
+ * odmoe.h -- C ABI of libodmoe.so: the cacheless Mixture-of-Experts decode layer
+ * of OD-MoE (arXiv 2512.03927) on one AMD MI355X (gfx950).
+ *
+ * What the calls compute.  Per token and per MoE layer (paper Section 3.1: the gating
+ * network "as in a standard MoE system", top-2 policy; Section 4.1: Mixtral-8x7B experts):
+ *
+ *   logit[e] = b[e] + sum_h Wg[e,h] x[h]                  (float64 sum, rounded once to fp32)
+ *   idx      = k largest logits, order (logit desc, index asc)       -- ties: lowest index wins
+ *   g_i      = exp(l_i - l_0) / sum_j exp(l_j - l_0)      over the k kept experts  (sum g = 1)
+ *   FFN_e(x) = W2_e ( silu(W1_e x) * (W3_e x) ),  silu(a) = a / (1 + exp(-a))
+ *   y        = sum_{i<k} g_i FFN_{idx_i}(x)               (fp32, i ascending, one final rounding)
+ *
+ * and, between stacked layers when config.glue = 1 (stand-in for the main node's non-expert
+ * work M_l of Section 3.1, which is outside this library):  x <- rmsnorm(x + y), eps 1e-6.
+ *
+ * Cacheless operation (paper Sections 1-3.1: experts live in CPU DRAM, an expert is loaded
+ * to the GPU on demand -- task EL_l -- used once -- task EC_l -- and evicted right after): with
+ * config.n_slots > 0 the experts' weights stay in pinned host memory and only n_slots
+ * expert-sized slots exist in HBM.  Every activation is a host->HBM copy; nothing is cached.
+ *
+ * Conventions.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *   - All matrices are row-major and dense.  dtype applies to x, y, router and expert weights;
+ *     bf16 is the upper 16 bits of an fp32 (round-to-nearest-even).
+ *   - One expert is ONE contiguous buffer:  W1[F,H] | W3[F,H] | W2[H,F]   (3*H*F elements).
+ *   - hidden and ffn must be multiples of 8; 1 <= top_k <= min(n_experts, 8); n_experts <= 1024.
+ *   - The caller owns every buffer it passes in; weight buffers must outlive the handle.
+ *     Streams are borrowed (never destroyed here).  The library owns its slot pool, scratch
+ *     buffers, events and, if none was given, its copy stream.
+ *   - Every call returns an odmoe_status.  Argument errors are detected before anything is
+ *     enqueued.  HIP errors are reported as ODMOE_EHIP by the call that observes them.
+ *     odmoe_last_error() gives a thread-local message for the last failing call.
+ *   - No call blocks the host except odmoe_decode_step (cacheless mode: once per layer, to
+ *     learn which experts to copy, and once at its end), odmoe_expert_ffn in cacheless mode
+ *     without idx_host, and odmoe_layer_destroy.
+ *   - A handle is not thread-safe: one host thread drives one handle.
+ */
+#ifndef ODMOE_H
+#define ODMOE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct odmoe_layer odmoe_layer_t; /* opaque: one stack of n_layers MoE layers */
+
+typedef enum {
+  ODMOE_OK = 0,
+  ODMOE_EINVAL = -1, /* bad argument (null pointer, out-of-range index, unsupported shape) */
+  ODMOE_ENOMEM = -2, /* device or host allocation failed */
+  ODMOE_EHIP = -3,   /* a HIP runtime call failed; see odmoe_last_error() */
+  ODMOE_ESTATE = -4, /* an expert that is needed is neither resident nor being loaded */
+  ODMOE_EBUSY = -5   /* no free slot for a load */
+} odmoe_status;
+
+typedef enum { ODMOE_F32 = 0, ODMOE_BF16 = 1 } odmoe_dtype;
+
+#define ODMOE_MAX_TOPK 8
+#define ODMOE_MAX_EXPERTS 1024
+
+typedef struct {
+  int32_t hidden;    /* H */
+  int32_t ffn;       /* F */
+  int32_t n_experts; /* E */
+  int32_t top_k;     /* k */
+  int32_t n_layers;  /* L */
+  int32_t n_slots;   /* S; 0 = resident: expert_w are DEVICE pointers and nothing is ever loaded */
+  int32_t dtype;     /* odmoe_dtype */
+  int32_t glue;      /* 0: x_{l+1} = y_l ; 1: x_{l+1} = rmsnorm(x_l + y_l) between stacked layers */
+} odmoe_config;
+
+typedef struct {
+  /* kernel / copy times are HIP-event times summed over the layers of one call; they are 0
+     unless timing was asked for (see odmoe_decode_step) */
+  float t_route_ms;    /* router GEMV + top-k gate kernel */
+  float t_load_ms;     /* host->HBM expert copies (copy stream) */
+  float t_ffn_up_ms;   /* w1/w3 GEMV + SiLU gate kernel */
+  float t_ffn_down_ms; /* w2 GEMV + weighted combine kernel */
+  float t_glue_ms;     /* inter-layer glue kernel */
+  float t_step_ms;     /* wall time of the call, host clock */
+  uint64_t h2d_bytes; /* bytes copied host->HBM by this call */
+  uint64_t loads;     /* expert loads issued by this call (cacheless: n_layers*top_k + reloads) */
+  uint64_t reloads;   /* loads caused by wrong predictions (Section 3.1: misprediction fallback) */
+  uint64_t hint_hits; /* predicted experts that the router confirmed */
+} odmoe_stats;
+
+/*
+ * Create a stack of L MoE layers (Section 3.1: gating network + experts; worker memory holds
+ * only the scheduled experts).
+ *   cfg         host pointer.
+ *   router_w    host array of L DEVICE pointers, each Wg[E,H] in cfg->dtype.
+ *   router_b    NULL, or host array of L DEVICE pointers (entries may be NULL), each b[E] fp32.
+ *   expert_w    host array of L*E pointers (index layer*E + expert), each one expert buffer.
+ *               n_slots == 0: DEVICE pointers.  n_slots > 0: HOST pointers to PINNED memory
+ *               (hipHostMalloc / torch pin_memory; odmoe_pinned_alloc provides it too).
+ *   compute_stream  hipStream_t as void*; NULL = the null stream.
+ *   copy_stream     hipStream_t for host->HBM copies; NULL = the library creates one.
+ *   out         receives the handle.
+ * Allocates S*expert_bytes of HBM for the slot pool plus small scratch.  n_slots > 0 needs
+ * n_slots >= top_k.  Returns EINVAL / ENOMEM / EHIP; on failure *out is NULL.
+ */
+int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w,
+                     const void* const* router_b, const void* const* expert_w,
+                     void* compute_stream, void* copy_stream, odmoe_layer_t** out);
+
+/* Waits for both streams, frees everything the library owns.  NULL is allowed. */
+int odmoe_layer_destroy(odmoe_layer_t* h);
+
+/*
+ * Router GEMV + top-k softmax gate (Section 3.1, gating network of layer `layer`) for
+ * n_tokens rows of x_dev[T,H].  Writes idx_dev[T,k] (int32) and gate_dev[T,k] (fp32).
+ * Asynchronous on the compute stream.  NaN logits give an unspecified selection.
+ */
+int odmoe_route_topk(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t n_tokens,
+                     int32_t* idx_dev, float* gate_dev);
+
+/*
+ * On-demand expert loading EL_l (Sections 1, 3.1): enqueue the copy of expert (layer, expert)
+ * from pinned host memory into a free HBM slot on the copy stream.  The copy waits (stream
+ * side) for the kernels that last read that slot.  If the expert is already loading or
+ * ready, its slot is returned and nothing is copied.  *slot_out (may be NULL) gets the slot.
+ * EBUSY when every slot is occupied; EINVAL in resident mode or for a bad index.
+ */
+int odmoe_expert_load_async(odmoe_layer_t* h, int32_t layer, int32_t expert, int32_t* slot_out);
+
+/* Drop expert (layer, expert) from its slot without using it (a wrongly predicted expert).
+ * ESTATE if it holds no slot. */
+int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert);
+
+/*
+ * Expert computation EC_l (Section 3.1) with the weighted combine, for n_tokens tokens:
+ *   y[t] = sum_i gate[t,i] * FFN_{idx[t,i]}(x[t]).
+ *   idx_dev[T,k], gate_dev[T,k], x_dev[T,H], y_dev[T,H] are device pointers.
+ *   idx_host   optional host copy of idx (cacheless mode needs to know the experts on the
+ *              host; when NULL there, the library reads idx_dev back and blocks for it).
+ *   n_tokens   < 16: one fused w1/w3+SiLU GEMV and one w2+combine GEMV per token;
+ *              >= 16 (bf16, resident): prefill path of Section 3.3 -- tokens are grouped by
+ *              expert and each expert runs a grouped GEMM on the matrix cores.
+ *   evict_after  cacheless mode: nonzero releases the experts' slots after the kernels that
+ *              read them (the paper's prompt eviction).  Ignored in resident mode.
+ * Cacheless mode supports n_tokens == 1 here.  The compute stream waits (stream side) for
+ * each needed expert's copy.  ESTATE if a needed expert is neither loading nor ready.
+ */
+int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev,
+                     const float* gate_dev, const int32_t* idx_host, const void* x_dev,
+                     int32_t n_tokens, void* y_dev, int32_t evict_after);
+
+/*
+ * One decode token through all L layers (Section 3.1 pipeline on one GPU):
+ * per layer  route -> learn ids on the host -> load the k experts -> FFN + combine -> evict
+ * -> glue.  x_dev[H] in, y_dev[H] out.  With glue = 0 the result is the last layer's y
+ * (and x_{l+1} = y_l in between); with glue = 1 it is the state after the last layer's glue,
+ * x_L = rmsnorm(x_{L-1} + y_{L-1}), each layer's y being rounded to dtype before the glue.
+ *   predicted_idx_host  NULL, or int32[L,k] predicted experts per layer (the role of the
+ *              shadow node's prediction): loads for coming layers are issued ahead as slots
+ *              allow; the router's result is authoritative; wrong predictions are evicted
+ *              and the right expert reloaded (misprediction fallback).  Predictions change
+ *              timing only, never y.
+ *   idx_out_host  NULL, or int32[L,k] receiving the experts actually used.
+ *   stats      NULL, or receives counters; kernel/copy times are measured only when
+ *              stats->t_step_ms is set to a negative value on entry (adds event overhead).
+ * Blocks until y is complete, except in resident mode with idx_out_host == NULL and
+ * stats == NULL, where the call only enqueues work on the compute stream (and no host
+ * synchronisation happens per layer either).
+ */
+int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
+                      const int32_t* predicted_idx_host, int32_t* idx_out_host,
+                      odmoe_stats* stats);
+
+/* Pinned host memory for the expert store (the workers' DRAM of Section 1). */
+int odmoe_pinned_alloc(uint64_t bytes, void** out_host);
+int odmoe_pinned_free(void* host);
+
+/* Bytes of HBM the handle's slot pool occupies (S * expert bytes); 0 in resident mode. */
+uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h);
+
+/* Thread-local message of the last failing call on this thread ("" if none). */
+const char* odmoe_last_error(void);
+
+/* Library version string. */
+const char* odmoe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ODMOE_H */

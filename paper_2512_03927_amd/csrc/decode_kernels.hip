@@ -1,0 +1,413 @@
+// Decode-path kernels for gfx950 (wave64): router + top-k gate, the two expert GEMVs with the
+// SiLU gate and the weighted combine, and the inter-layer glue.
+//
+// The expert GEMVs are bound by HBM bandwidth (one multiply-add per weight element, every weight
+// read exactly once per token), so they use 128-bit non-temporal loads, keep the input vector in
+// LDS as fp32 and never touch the matrix cores.
+#include "kernels.h"
+
+namespace odmoe {
+namespace {
+
+constexpr int WAVE = 64;
+typedef uint16_t bf16_t;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (finite values).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T>
+struct DT;
+template <>
+struct DT<float> {
+  static constexpr int VEC = 4;  // elements per 128-bit load
+  static __device__ __forceinline__ void unpack(u32x4 q, float* f) {
+    f[0] = __uint_as_float(q.x); f[1] = __uint_as_float(q.y);
+    f[2] = __uint_as_float(q.z); f[3] = __uint_as_float(q.w);
+  }
+  static __device__ __forceinline__ float to_f32(float v) { return v; }
+  static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <>
+struct DT<bf16_t> {
+  static constexpr int VEC = 8;
+  static __device__ __forceinline__ void unpack(u32x4 q, float* f) {
+    f[0] = bf16_lo(q.x); f[1] = bf16_hi(q.x); f[2] = bf16_lo(q.y); f[3] = bf16_hi(q.y);
+    f[4] = bf16_lo(q.z); f[5] = bf16_hi(q.z); f[6] = bf16_lo(q.w); f[7] = bf16_hi(q.w);
+  }
+  static __device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
+  static __device__ __forceinline__ bf16_t from_f32(float v) { return f32_to_bf16(v); }
+};
+
+template <typename T>
+__device__ __forceinline__ u32x4 load16(const T* p) {
+  return *reinterpret_cast<const u32x4*>(p);
+}
+// Streaming load for weights: each byte is used once, keep it out of the way of reused lines.
+template <typename T>
+__device__ __forceinline__ u32x4 load16_stream(const T* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+  return v;
+}
+
+__device__ __forceinline__ const void* expert_ptr(const ExpertSrc& s, const int32_t* idx, int i) {
+  return s.table ? s.table[s.table_off + idx[i]] : s.slot[i];
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS layout of an fp32 vector that 128-bit weight loads are multiplied with.  Vector element
+// group v (VEC consecutive elements, the ones lane v%64 of chunk v/64 multiplies) is stored so
+// that every ds_read_b128 of a wave touches 64 consecutive float4s:
+//   VEC = 4 :  float4 at  chunk*256 + lane*4
+//   VEC = 8 :  float4 at  chunk*512 + lane*4  and  chunk*512 + 256 + lane*4
+// ---------------------------------------------------------------------------------------------
+template <int VEC>
+__device__ __forceinline__ int lds_pos(int v, int half) {
+  return (v >> 6) * (WAVE * VEC) + half * (WAVE * 4) + (v & 63) * 4;
+}
+
+// dot( row[0:n], vec ) over one wave; vec is in LDS in the layout above; n % VEC == 0.
+template <typename T>
+__device__ __forceinline__ float wave_dot(const T* __restrict__ row, const float* __restrict__ svec,
+                                          int nvec, int lane) {
+  constexpr int VEC = DT<T>::VEC;
+  float acc = 0.f;
+  int v = lane;
+#pragma unroll 4
+  for (; v < nvec; v += WAVE) {
+    u32x4 q = load16_stream(row + (size_t)v * VEC);
+    float f[VEC];
+    DT<T>::unpack(q, f);
+    f32x4 a = *reinterpret_cast<const f32x4*>(svec + lds_pos<VEC>(v, 0));
+    acc = fmaf(f[0], a.x, acc); acc = fmaf(f[1], a.y, acc);
+    acc = fmaf(f[2], a.z, acc); acc = fmaf(f[3], a.w, acc);
+    if constexpr (VEC == 8) {
+      f32x4 b = *reinterpret_cast<const f32x4*>(svec + lds_pos<VEC>(v, 1));
+      acc = fmaf(f[4], b.x, acc); acc = fmaf(f[5], b.y, acc);
+      acc = fmaf(f[6], b.z, acc); acc = fmaf(f[7], b.w, acc);
+    }
+  }
+  return wave_sum(acc);
+}
+
+// Two rows against the same vector (the w1 / w3 pair): twice the loads in flight per wave.
+template <typename T>
+__device__ __forceinline__ void wave_dot2(const T* __restrict__ row_a, const T* __restrict__ row_b,
+                                          const float* __restrict__ svec, int nvec, int lane,
+                                          float& out_a, float& out_b) {
+  constexpr int VEC = DT<T>::VEC;
+  float acc_a = 0.f, acc_b = 0.f;
+#pragma unroll 4
+  for (int v = lane; v < nvec; v += WAVE) {
+    u32x4 qa = load16_stream(row_a + (size_t)v * VEC);
+    u32x4 qb = load16_stream(row_b + (size_t)v * VEC);
+    float fa[VEC], fb[VEC];
+    DT<T>::unpack(qa, fa);
+    DT<T>::unpack(qb, fb);
+    f32x4 x0 = *reinterpret_cast<const f32x4*>(svec + lds_pos<VEC>(v, 0));
+    acc_a = fmaf(fa[0], x0.x, acc_a); acc_a = fmaf(fa[1], x0.y, acc_a);
+    acc_a = fmaf(fa[2], x0.z, acc_a); acc_a = fmaf(fa[3], x0.w, acc_a);
+    acc_b = fmaf(fb[0], x0.x, acc_b); acc_b = fmaf(fb[1], x0.y, acc_b);
+    acc_b = fmaf(fb[2], x0.z, acc_b); acc_b = fmaf(fb[3], x0.w, acc_b);
+    if constexpr (VEC == 8) {
+      f32x4 x1 = *reinterpret_cast<const f32x4*>(svec + lds_pos<VEC>(v, 1));
+      acc_a = fmaf(fa[4], x1.x, acc_a); acc_a = fmaf(fa[5], x1.y, acc_a);
+      acc_a = fmaf(fa[6], x1.z, acc_a); acc_a = fmaf(fa[7], x1.w, acc_a);
+      acc_b = fmaf(fb[4], x1.x, acc_b); acc_b = fmaf(fb[5], x1.y, acc_b);
+      acc_b = fmaf(fb[6], x1.z, acc_b); acc_b = fmaf(fb[7], x1.w, acc_b);
+    }
+  }
+  out_a = wave_sum(acc_a);
+  out_b = wave_sum(acc_b);
+}
+
+// Stage n elements of a stored-dtype vector into LDS as fp32 (layout above).  n % VEC == 0.
+template <typename T, int VEC_OF_WEIGHTS>
+__device__ __forceinline__ void stage_vec(const T* __restrict__ src, float* __restrict__ svec, int n) {
+  constexpr int SV = DT<T>::VEC;  // elements per 128-bit load of the source
+  for (int s = threadIdx.x; s * SV < n; s += blockDim.x) {
+    float f[SV];
+    DT<T>::unpack(load16(src + (size_t)s * SV), f);
+#pragma unroll
+    for (int q = 0; q < SV / 4; ++q) {
+      int f4 = s * (SV / 4) + q;  // index of this float4 in the source vector
+      int v, half;
+      if constexpr (VEC_OF_WEIGHTS == 8) { v = f4 >> 1; half = f4 & 1; } else { v = f4; half = 0; }
+      *reinterpret_cast<f32x4*>(svec + lds_pos<VEC_OF_WEIGHTS>(v, half)) =
+          f32x4{f[4 * q], f[4 * q + 1], f[4 * q + 2], f[4 * q + 3]};
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Router GEMV + top-k + renormalised softmax gate.  One block per token.
+// Logits are summed in float64 and rounded once to fp32, so the selection agrees with a float64
+// reference rounded the same way regardless of summation order.  Ties: lowest index first.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void route_topk_kernel(const T* __restrict__ Wg,
+                                                          const float* __restrict__ bias,
+                                                          const T* __restrict__ x, int H, int E, int k,
+                                                          int32_t* __restrict__ idx,
+                                                          float* __restrict__ gate,
+                                                          int32_t* __restrict__ idx_mirror) {
+  constexpr int VEC = DT<T>::VEC;
+  __shared__ float slog[ODMOE_MAX_EXPERTS];
+  const int t = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const T* xt = x + (size_t)t * H;
+  const int nvec = H / VEC;
+  for (int e = wave; e < E; e += nw) {
+    const T* row = Wg + (size_t)e * H;
+    double acc = 0.0;
+    for (int v = lane; v < nvec; v += WAVE) {
+      float fw[VEC], fx[VEC];
+      DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
+      DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) acc = fma((double)fw[j], (double)fx[j], acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) slog[e] = (float)(acc + (bias ? (double)bias[e] : 0.0));
+  }
+  __syncthreads();
+  if (wave != 0) return;
+
+  // k rounds of "best element strictly after the previous pick" in the total order
+  // (logit descending, index ascending).
+  const int NONE = 0x7fffffff;
+  float prev_v = 0.f, my_v = 0.f;
+  int prev_i = -1, my_i = 0;
+  for (int i = 0; i < k; ++i) {
+    float bv = 0.f;
+    int bi = NONE;
+    for (int e = lane; e < E; e += WAVE) {
+      float v = slog[e];
+      bool after = (i == 0) || (v < prev_v) || (v == prev_v && e > prev_i);
+      bool better = (bi == NONE) || (v > bv) || (v == bv && e < bi);
+      if (after && better) { bv = v; bi = e; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      float ov = __shfl_xor(bv, off, WAVE);
+      int oi = __shfl_xor(bi, off, WAVE);
+      bool take = (oi != NONE) && ((bi == NONE) || (ov > bv) || (ov == bv && oi < bi));
+      if (take) { bv = ov; bi = oi; }
+    }
+    prev_v = bv; prev_i = bi;
+    if (lane == i) { my_v = bv; my_i = bi; }
+  }
+  const float v0 = __shfl(my_v, 0, WAVE);
+  const float u = (lane < k) ? expf(my_v - v0) : 0.f;
+  float s = 0.f;
+  for (int i = 0; i < k; ++i) s += __shfl(u, i, WAVE);  // fixed order i = 0..k-1
+  if (lane < k) {
+    idx[(size_t)t * k + lane] = my_i;
+    gate[(size_t)t * k + lane] = u / s;
+    if (idx_mirror) idx_mirror[(size_t)t * k + lane] = my_i;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// h[i, j] = silu(W1_i[j,:] . x) * (W3_i[j,:] . x)  for the k selected experts of one token.
+// One wave per (expert rank, ffn row) pair; RPW consecutive pairs per wave.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int RPW>
+__global__ __launch_bounds__(256) void ffn_up_kernel(ExpertSrc src, const int32_t* __restrict__ idx,
+                                                      const T* __restrict__ x,
+                                                      float* __restrict__ hbuf, int H, int F, int k) {
+  constexpr int VEC = DT<T>::VEC;
+  extern __shared__ float svec[];
+  stage_vec<T, VEC>(x, svec, H);
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int nvec = H / VEC;
+  const long total = (long)k * F;
+  const long r0 = ((long)blockIdx.x * nw + wave) * RPW;
+#pragma unroll 1
+  for (int rr = 0; rr < RPW; ++rr) {
+    const long r = r0 + rr;
+    if (r >= total) break;
+    const int i = (int)(r / F), j = (int)(r % F);
+    const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
+    const T* w1 = base + (size_t)j * H;
+    const T* w3 = base + (size_t)F * H + (size_t)j * H;
+    float a, b;
+    wave_dot2<T>(w1, w3, svec, nvec, lane, a, b);
+    if (lane == 0) hbuf[r] = a / (1.f + expf(-a)) * b;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// y[r] = sum_i gate[i] * (W2_i[r,:] . h_i)   -- w2 GEMV with the weighted combine fused, no
+// atomics: the block that owns output row r walks the k experts in order.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int RPW>
+__global__ __launch_bounds__(512) void ffn_down_kernel(ExpertSrc src, const int32_t* __restrict__ idx,
+                                                        const float* __restrict__ gate,
+                                                        const float* __restrict__ hbuf,
+                                                        T* __restrict__ y, int H, int F, int k) {
+  constexpr int VEC = DT<T>::VEC;
+  extern __shared__ float svec[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int nvec = F / VEC;
+  const int r0 = (blockIdx.x * nw + wave) * RPW;
+  float acc[RPW];
+#pragma unroll
+  for (int rr = 0; rr < RPW; ++rr) acc[rr] = 0.f;
+  for (int i = 0; i < k; ++i) {
+    if (i) __syncthreads();
+    stage_vec<float, VEC>(hbuf + (size_t)i * F, svec, F);
+    __syncthreads();
+    const float g = gate[i];
+    const T* w2 = static_cast<const T*>(expert_ptr(src, idx, i)) + (size_t)2 * F * H;
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+      const int r = r0 + rr;
+      if (r < H) {
+        float d = wave_dot<T>(w2 + (size_t)r * F, svec, nvec, lane);
+        acc[rr] = fmaf(g, d, acc[rr]);
+      }
+    }
+  }
+  if (lane == 0) {
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr)
+      if (r0 + rr < H) y[r0 + rr] = DT<T>::from_f32(acc[rr]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inter-layer glue: out = (x + y) / sqrt(mean((x + y)^2) + 1e-6).  One block.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(1024) void glue_kernel(const T* x, const T* y, T* out, int H) {
+  __shared__ float part[16];
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < H; i += blockDim.x) {
+    float z = DT<T>::to_f32(x[i]) + DT<T>::to_f32(y[i]);
+    ss = fmaf(z, z, ss);
+  }
+  ss = wave_sum(ss);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  if (lane == 0) part[wave] = ss;
+  __syncthreads();
+  float tot = 0.f;
+  for (int w = 0; w < nw; ++w) tot += part[w];
+  const float scale = 1.f / sqrtf(tot / (float)H + 1e-6f);
+  for (int i = threadIdx.x; i < H; i += blockDim.x) {
+    float z = DT<T>::to_f32(x[i]) + DT<T>::to_f32(y[i]);
+    out[i] = DT<T>::from_f32(z * scale);
+  }
+}
+
+inline size_t lds_vec_bytes(int n, int vec) {
+  const int chunk = WAVE * vec;
+  return (size_t)((n + chunk - 1) / chunk) * chunk * sizeof(float);
+}
+
+constexpr int UP_RPW = 4;
+constexpr int DOWN_RPW = 2;
+constexpr int UP_THREADS = 256;
+constexpr int DOWN_THREADS = 512;
+constexpr size_t MAX_LDS = 160 * 1024;
+
+}  // namespace
+
+hipError_t kernels_init() {
+  hipError_t e;
+  const int big = (int)MAX_LDS;
+#define ODMOE_SET_LDS(fn)                                                                    \
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(fn),                                 \
+                          hipFuncAttributeMaxDynamicSharedMemorySize, big);                  \
+  if (e != hipSuccess) return e;
+  ODMOE_SET_LDS((ffn_up_kernel<float, UP_RPW>));
+  ODMOE_SET_LDS((ffn_up_kernel<bf16_t, UP_RPW>));
+  ODMOE_SET_LDS((ffn_down_kernel<float, DOWN_RPW>));
+  ODMOE_SET_LDS((ffn_down_kernel<bf16_t, DOWN_RPW>));
+#undef ODMOE_SET_LDS
+  return hipSuccess;
+}
+
+hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
+                             const void* x, int32_t T, int32_t* idx, float* gate,
+                             int32_t* idx_mirror) {
+  if (T <= 0) return hipSuccess;
+  if (sh.dtype == ODMOE_F32)
+    route_topk_kernel<float><<<T, 256, 0, s>>>(static_cast<const float*>(Wg), b,
+                                               static_cast<const float*>(x), sh.H, sh.E, sh.k, idx,
+                                               gate, idx_mirror);
+  else
+    route_topk_kernel<bf16_t><<<T, 256, 0, s>>>(static_cast<const bf16_t*>(Wg), b,
+                                                static_cast<const bf16_t*>(x), sh.H, sh.E, sh.k,
+                                                idx, gate, idx_mirror);
+  return hipGetLastError();
+}
+
+hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                         const void* x, float* hbuf) {
+  const int nw = UP_THREADS / WAVE;
+  const long total = (long)sh.k * sh.F;
+  const int grid = (int)((total + nw * UP_RPW - 1) / (nw * UP_RPW));
+  if (sh.dtype == ODMOE_F32) {
+    const size_t lds = lds_vec_bytes(sh.H, 4);
+    if (lds > MAX_LDS) return hipErrorInvalidValue;
+    ffn_up_kernel<float, UP_RPW><<<grid, UP_THREADS, lds, s>>>(src, idx, static_cast<const float*>(x),
+                                                               hbuf, sh.H, sh.F, sh.k);
+  } else {
+    const size_t lds = lds_vec_bytes(sh.H, 8);
+    if (lds > MAX_LDS) return hipErrorInvalidValue;
+    ffn_up_kernel<bf16_t, UP_RPW><<<grid, UP_THREADS, lds, s>>>(src, idx, static_cast<const bf16_t*>(x),
+                                                                hbuf, sh.H, sh.F, sh.k);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
+                           const int32_t* idx, const float* gate, const float* hbuf, void* y) {
+  const int nw = DOWN_THREADS / WAVE;
+  const int grid = (sh.H + nw * DOWN_RPW - 1) / (nw * DOWN_RPW);
+  if (sh.dtype == ODMOE_F32) {
+    const size_t lds = lds_vec_bytes(sh.F, 4);
+    if (lds > MAX_LDS) return hipErrorInvalidValue;
+    ffn_down_kernel<float, DOWN_RPW><<<grid, DOWN_THREADS, lds, s>>>(
+        src, idx, gate, hbuf, static_cast<float*>(y), sh.H, sh.F, sh.k);
+  } else {
+    const size_t lds = lds_vec_bytes(sh.F, 8);
+    if (lds > MAX_LDS) return hipErrorInvalidValue;
+    ffn_down_kernel<bf16_t, DOWN_RPW><<<grid, DOWN_THREADS, lds, s>>>(
+        src, idx, gate, hbuf, static_cast<bf16_t*>(y), sh.H, sh.F, sh.k);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_glue(hipStream_t s, const Shape& sh, const void* x, const void* y, void* x_next) {
+  if (sh.dtype == ODMOE_F32)
+    glue_kernel<float><<<1, 1024, 0, s>>>(static_cast<const float*>(x), static_cast<const float*>(y),
+                                          static_cast<float*>(x_next), sh.H);
+  else
+    glue_kernel<bf16_t><<<1, 1024, 0, s>>>(static_cast<const bf16_t*>(x),
+                                           static_cast<const bf16_t*>(y),
+                                           static_cast<bf16_t*>(x_next), sh.H);
+  return hipGetLastError();
+}
+
+}  // namespace odmoe

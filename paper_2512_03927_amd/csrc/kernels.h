@@ -1,0 +1,52 @@
+// Internal launcher interface between the C-ABI layer and the HIP kernels.
+// Not part of the public boundary (that is include/odmoe.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/odmoe.h"
+
+namespace odmoe {
+
+// Where the weights of the i-th selected expert (rank i in idx) live.
+//   resident : table != nullptr, pointer = table[table_off + idx[t*k + i]]   (device table, L*E entries)
+//   cacheless: table == nullptr, pointer = slot[i]                           (HBM slot bases by rank)
+struct ExpertSrc {
+  const void* slot[ODMOE_MAX_TOPK];
+  const void* const* table;
+  int32_t table_off;
+};
+
+struct Shape {
+  int32_t H, F, E, k;
+  int32_t dtype;  // odmoe_dtype
+};
+
+// Router GEMV + top-k + gate for T tokens.  idx_mirror (may be null) is a second int32[T*k]
+// destination (host-mapped pinned memory) written together with idx.
+hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
+                             const void* x, int32_t T, int32_t* idx, float* gate,
+                             int32_t* idx_mirror);
+
+// h[i, :] = silu(W1 x) * (W3 x) for the k selected experts of ONE token.  hbuf: fp32 [k, F].
+hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                         const void* x, float* hbuf);
+
+// y = sum_i gate[i] * (W2_i h_i) for ONE token; y in sh.dtype [H].
+hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
+                           const int32_t* idx, const float* gate, const float* hbuf, void* y);
+
+// glue = 1: x_next = rmsnorm(x + y) (eps 1e-6).  All [H] in sh.dtype.
+hipError_t launch_glue(hipStream_t s, const Shape& sh, const void* x, const void* y, void* x_next);
+
+// Prefill (bf16, resident): tokens grouped by expert, grouped GEMMs on the matrix cores.
+// Workspace sizes in bytes for T tokens; the workspace is carved by the launcher.
+size_t prefill_workspace_bytes(const Shape& sh, int32_t T);
+hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* table,
+                          int32_t table_off, const int32_t* idx, const float* gate, const void* x,
+                          int32_t T, void* y, void* workspace, size_t workspace_bytes);
+
+// One-time per-process kernel attribute setup (large dynamic LDS).
+hipError_t kernels_init();
+
+}  // namespace odmoe

@@ -1,0 +1,523 @@
+// C-ABI of libodmoe.so (declared in include/odmoe.h): handle, slot pool + copy engine,
+// and the per-token decode loop.  All arithmetic lives in the kernels; this file only
+// validates, schedules and enqueues.
+#include <hip/hip_runtime.h>
+
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "sched.hpp"
+
+using namespace odmoe;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e__ = (expr);                                                               \
+    if (e__ != hipSuccess)                                                                 \
+      return fail(ODMOE_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__),      \
+                  __FILE__, __LINE__);                                                     \
+  } while (0)
+
+size_t dtype_size(int32_t dt) { return dt == ODMOE_F32 ? 4 : 2; }
+
+}  // namespace
+
+struct odmoe_layer {
+  odmoe_config cfg{};
+  Shape sh{};
+  size_t esize = 0;         // bytes per element
+  size_t expert_bytes = 0;  // 3*H*F*esize
+  hipStream_t compute = nullptr, copy = nullptr;
+  bool own_copy = false;
+
+  std::vector<const void*> router_w, router_b, expert_w;  // host copies of the pointer arrays
+  const void** table_dev = nullptr;                        // resident: device table [L*E]
+
+  // cacheless state
+  char* pool_mem = nullptr;
+  SlotPool* pool = nullptr;
+  DecodeScheduler* sched = nullptr;
+  std::vector<hipEvent_t> ready_ev, done_ev;  // per slot
+  std::vector<char> done_pending;             // done_ev[slot] recorded since the slot's last copy
+
+  // scratch
+  float* hbuf = nullptr;      // [k*F] fp32
+  void* xbuf[2] = {nullptr, nullptr};
+  void* ybuf = nullptr;       // [H]
+  int32_t* idx_dev = nullptr;   // [L*k]
+  float* gate_dev = nullptr;    // [L*k]
+  int32_t* idx_pin = nullptr;   // pinned host [L*k], written by the router kernel
+  int32_t* idx_pin_dev = nullptr;
+  hipEvent_t route_ev = nullptr;
+  void* prefill_ws = nullptr;
+  size_t prefill_ws_bytes = 0;
+
+  // optional timing events (created on first timed decode_step): [L] pairs
+  std::vector<hipEvent_t> tev;  // 5 per layer: route begin, up begin, down begin, glue begin, end
+  std::vector<hipEvent_t> lev;  // 2 per load (begin/end on the copy stream), room for 2*L*k loads
+};
+
+namespace {
+
+int validate_cfg(const odmoe_config* c) {
+  if (!c) return fail(ODMOE_EINVAL, "cfg is NULL");
+  if (c->hidden <= 0 || c->ffn <= 0 || c->hidden % 8 || c->ffn % 8)
+    return fail(ODMOE_EINVAL, "hidden (%d) and ffn (%d) must be positive multiples of 8", c->hidden, c->ffn);
+  if (c->n_experts < 1 || c->n_experts > ODMOE_MAX_EXPERTS)
+    return fail(ODMOE_EINVAL, "n_experts %d out of range [1, %d]", c->n_experts, ODMOE_MAX_EXPERTS);
+  if (c->top_k < 1 || c->top_k > ODMOE_MAX_TOPK || c->top_k > c->n_experts)
+    return fail(ODMOE_EINVAL, "top_k %d out of range [1, min(E, %d)]", c->top_k, ODMOE_MAX_TOPK);
+  if (c->n_layers < 1) return fail(ODMOE_EINVAL, "n_layers %d < 1", c->n_layers);
+  if (c->n_slots < 0 || (c->n_slots > 0 && c->n_slots < c->top_k))
+    return fail(ODMOE_EINVAL, "n_slots %d must be 0 (resident) or >= top_k", c->n_slots);
+  if (c->dtype != ODMOE_F32 && c->dtype != ODMOE_BF16) return fail(ODMOE_EINVAL, "bad dtype %d", c->dtype);
+  if (c->glue != 0 && c->glue != 1) return fail(ODMOE_EINVAL, "bad glue %d", c->glue);
+  // the GEMV kernels keep one fp32 input vector in LDS (160 KB per workgroup on gfx950)
+  const long max_vec = 160 * 1024 / 4;
+  const long chunk = c->dtype == ODMOE_F32 ? 256 : 512;
+  if (((c->hidden + chunk - 1) / chunk) * chunk > max_vec || ((c->ffn + chunk - 1) / chunk) * chunk > max_vec)
+    return fail(ODMOE_EINVAL, "hidden/ffn above %ld elements do not fit the LDS-staged GEMV", max_vec);
+  return ODMOE_OK;
+}
+
+void free_all(odmoe_layer* h) {
+  if (!h) return;
+  for (auto e : h->ready_ev) if (e) (void)hipEventDestroy(e);
+  for (auto e : h->done_ev) if (e) (void)hipEventDestroy(e);
+  for (auto e : h->tev) if (e) (void)hipEventDestroy(e);
+  for (auto e : h->lev) if (e) (void)hipEventDestroy(e);
+  if (h->route_ev) (void)hipEventDestroy(h->route_ev);
+  if (h->pool_mem) (void)hipFree(h->pool_mem);
+  if (h->table_dev) (void)hipFree((void*)h->table_dev);
+  if (h->hbuf) (void)hipFree(h->hbuf);
+  if (h->xbuf[0]) (void)hipFree(h->xbuf[0]);
+  if (h->xbuf[1]) (void)hipFree(h->xbuf[1]);
+  if (h->ybuf) (void)hipFree(h->ybuf);
+  if (h->idx_dev) (void)hipFree(h->idx_dev);
+  if (h->gate_dev) (void)hipFree(h->gate_dev);
+  if (h->idx_pin) (void)hipHostFree(h->idx_pin);
+  if (h->prefill_ws) (void)hipFree(h->prefill_ws);
+  if (h->own_copy && h->copy) (void)hipStreamDestroy(h->copy);
+  delete h->sched;
+  delete h->pool;
+  delete h;
+}
+
+int check_layer(const odmoe_layer* h, int32_t layer) {
+  if (!h) return fail(ODMOE_EINVAL, "handle is NULL");
+  if (layer < 0 || layer >= h->cfg.n_layers)
+    return fail(ODMOE_EINVAL, "layer %d out of range [0, %d)", layer, h->cfg.n_layers);
+  return ODMOE_OK;
+}
+
+// Enqueue the copy of (layer, expert) into `slot` on the copy stream.
+int enqueue_load(odmoe_layer* h, int32_t layer, int32_t expert, int32_t slot, hipEvent_t t0 = nullptr,
+                 hipEvent_t t1 = nullptr) {
+  if (h->done_pending[slot]) {
+    HIP_TRY(hipStreamWaitEvent(h->copy, h->done_ev[slot], 0));
+    h->done_pending[slot] = 0;
+  }
+  const void* src = h->expert_w[(size_t)layer * h->cfg.n_experts + expert];
+  if (t0) HIP_TRY(hipEventRecord(t0, h->copy));
+  HIP_TRY(hipMemcpyAsync(h->pool_mem + (size_t)slot * h->expert_bytes, src, h->expert_bytes,
+                         hipMemcpyHostToDevice, h->copy));
+  if (t1) HIP_TRY(hipEventRecord(t1, h->copy));
+  HIP_TRY(hipEventRecord(h->ready_ev[slot], h->copy));
+  return ODMOE_OK;
+}
+
+// The kernels that read `slot` have been enqueued on the compute stream: the slot may be
+// overwritten once they are done.
+int mark_used(odmoe_layer* h, int32_t slot) {
+  HIP_TRY(hipEventRecord(h->done_ev[slot], h->compute));
+  h->done_pending[slot] = 1;
+  return ODMOE_OK;
+}
+
+int run_ffn_one_token(odmoe_layer* h, const ExpertSrc& src, const int32_t* idx_dev,
+                      const float* gate_dev, const void* x, void* y, hipEvent_t between = nullptr) {
+  HIP_TRY(launch_ffn_up(h->compute, h->sh, src, idx_dev, x, h->hbuf));
+  if (between) HIP_TRY(hipEventRecord(between, h->compute));
+  HIP_TRY(launch_ffn_down(h->compute, h->sh, src, idx_dev, gate_dev, h->hbuf, y));
+  return ODMOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* odmoe_last_error(void) { return g_err.c_str(); }
+const char* odmoe_version(void) { return "odmoe 0.1 (gfx950)"; }
+
+int odmoe_pinned_alloc(uint64_t bytes, void** out_host) {
+  if (!out_host || bytes == 0) return fail(ODMOE_EINVAL, "bad arguments");
+  *out_host = nullptr;
+  hipError_t e = hipHostMalloc(out_host, bytes, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    *out_host = nullptr;
+    return fail(ODMOE_ENOMEM, "hipHostMalloc(%llu) failed: %s", (unsigned long long)bytes, hipGetErrorString(e));
+  }
+  return ODMOE_OK;
+}
+
+int odmoe_pinned_free(void* host) {
+  if (!host) return ODMOE_OK;
+  HIP_TRY(hipHostFree(host));
+  return ODMOE_OK;
+}
+
+uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h) {
+  return h && h->pool ? (uint64_t)h->cfg.n_slots * h->expert_bytes : 0;
+}
+
+int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const void* const* router_b,
+                     const void* const* expert_w, void* compute_stream, void* copy_stream,
+                     odmoe_layer_t** out) {
+  if (!out) return fail(ODMOE_EINVAL, "out is NULL");
+  *out = nullptr;
+  int rc = validate_cfg(cfg);
+  if (rc) return rc;
+  if (!router_w || !expert_w) return fail(ODMOE_EINVAL, "router_w / expert_w is NULL");
+  const int L = cfg->n_layers, E = cfg->n_experts, k = cfg->top_k, S = cfg->n_slots;
+  for (int l = 0; l < L; ++l)
+    if (!router_w[l]) return fail(ODMOE_EINVAL, "router_w[%d] is NULL", l);
+  for (long i = 0; i < (long)L * E; ++i)
+    if (!expert_w[i]) return fail(ODMOE_EINVAL, "expert_w[%ld] is NULL", i);
+
+  odmoe_layer* h = new (std::nothrow) odmoe_layer();
+  if (!h) return fail(ODMOE_ENOMEM, "out of host memory");
+  h->cfg = *cfg;
+  h->sh = Shape{cfg->hidden, cfg->ffn, E, k, cfg->dtype};
+  h->esize = dtype_size(cfg->dtype);
+  h->expert_bytes = (size_t)3 * cfg->hidden * cfg->ffn * h->esize;
+  h->compute = static_cast<hipStream_t>(compute_stream);
+  h->router_w.assign(router_w, router_w + L);
+  h->router_b.assign(L, nullptr);
+  if (router_b) h->router_b.assign(router_b, router_b + L);
+  h->expert_w.assign(expert_w, expert_w + (size_t)L * E);
+
+#define INIT_TRY(expr, code)                                                                    \
+  do {                                                                                          \
+    hipError_t e__ = (expr);                                                                    \
+    if (e__ != hipSuccess) {                                                                    \
+      int c__ = fail(code, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+      free_all(h);                                                                              \
+      return c__;                                                                               \
+    }                                                                                           \
+  } while (0)
+
+  INIT_TRY(kernels_init(), ODMOE_EHIP);
+  const size_t H = cfg->hidden, F = cfg->ffn;
+  INIT_TRY(hipMalloc(&h->hbuf, (size_t)k * F * sizeof(float)), ODMOE_ENOMEM);
+  INIT_TRY(hipMalloc(&h->xbuf[0], H * h->esize), ODMOE_ENOMEM);
+  INIT_TRY(hipMalloc(&h->xbuf[1], H * h->esize), ODMOE_ENOMEM);
+  INIT_TRY(hipMalloc(&h->ybuf, H * h->esize), ODMOE_ENOMEM);
+  INIT_TRY(hipMalloc(&h->idx_dev, (size_t)L * k * sizeof(int32_t)), ODMOE_ENOMEM);
+  INIT_TRY(hipMalloc(&h->gate_dev, (size_t)L * k * sizeof(float)), ODMOE_ENOMEM);
+  INIT_TRY(hipHostMalloc((void**)&h->idx_pin, (size_t)L * k * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent),
+           ODMOE_ENOMEM);
+  INIT_TRY(hipHostGetDevicePointer((void**)&h->idx_pin_dev, h->idx_pin, 0), ODMOE_EHIP);
+  INIT_TRY(hipEventCreateWithFlags(&h->route_ev, hipEventDisableTiming), ODMOE_EHIP);
+
+  if (S == 0) {
+    INIT_TRY(hipMalloc((void**)&h->table_dev, (size_t)L * E * sizeof(void*)), ODMOE_ENOMEM);
+    INIT_TRY(hipMemcpy((void*)h->table_dev, h->expert_w.data(), (size_t)L * E * sizeof(void*),
+                       hipMemcpyHostToDevice),
+             ODMOE_EHIP);
+  } else {
+    INIT_TRY(hipMalloc((void**)&h->pool_mem, (size_t)S * h->expert_bytes), ODMOE_ENOMEM);
+    h->pool = new SlotPool(S);
+    h->sched = new DecodeScheduler(L, E, k, h->pool);
+    h->ready_ev.assign(S, nullptr);
+    h->done_ev.assign(S, nullptr);
+    h->done_pending.assign(S, 0);
+    for (int s = 0; s < S; ++s) {
+      INIT_TRY(hipEventCreateWithFlags(&h->ready_ev[s], hipEventDisableTiming), ODMOE_EHIP);
+      INIT_TRY(hipEventCreateWithFlags(&h->done_ev[s], hipEventDisableTiming), ODMOE_EHIP);
+    }
+    if (copy_stream) {
+      h->copy = static_cast<hipStream_t>(copy_stream);
+    } else {
+      INIT_TRY(hipStreamCreateWithFlags(&h->copy, hipStreamNonBlocking), ODMOE_EHIP);
+      h->own_copy = true;
+    }
+  }
+#undef INIT_TRY
+  *out = h;
+  return ODMOE_OK;
+}
+
+int odmoe_layer_destroy(odmoe_layer_t* h) {
+  if (!h) return ODMOE_OK;
+  hipError_t e1 = hipStreamSynchronize(h->compute);
+  hipError_t e2 = h->copy ? hipStreamSynchronize(h->copy) : hipSuccess;
+  free_all(h);
+  if (e1 != hipSuccess) return fail(ODMOE_EHIP, "compute stream: %s", hipGetErrorString(e1));
+  if (e2 != hipSuccess) return fail(ODMOE_EHIP, "copy stream: %s", hipGetErrorString(e2));
+  return ODMOE_OK;
+}
+
+int odmoe_route_topk(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t n_tokens,
+                     int32_t* idx_dev, float* gate_dev) {
+  int rc = check_layer(h, layer);
+  if (rc) return rc;
+  if (n_tokens < 0) return fail(ODMOE_EINVAL, "n_tokens %d < 0", n_tokens);
+  if (n_tokens == 0) return ODMOE_OK;
+  if (!x_dev || !idx_dev || !gate_dev) return fail(ODMOE_EINVAL, "x/idx/gate is NULL");
+  HIP_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer],
+                            static_cast<const float*>(h->router_b[layer]), x_dev, n_tokens, idx_dev,
+                            gate_dev, nullptr));
+  return ODMOE_OK;
+}
+
+int odmoe_expert_load_async(odmoe_layer_t* h, int32_t layer, int32_t expert, int32_t* slot_out) {
+  int rc = check_layer(h, layer);
+  if (rc) return rc;
+  if (!h->pool) return fail(ODMOE_EINVAL, "resident mode: nothing to load");
+  if (expert < 0 || expert >= h->cfg.n_experts)
+    return fail(ODMOE_EINVAL, "expert %d out of range [0, %d)", expert, h->cfg.n_experts);
+  int s = h->pool->find(layer, expert);
+  if (s < 0) {
+    s = h->pool->acquire(layer, expert);
+    if (s < 0) return fail(ODMOE_EBUSY, "all %d slots are occupied", h->cfg.n_slots);
+    rc = enqueue_load(h, layer, expert, s);
+    if (rc) {
+      h->pool->release(s);
+      return rc;
+    }
+  }
+  if (slot_out) *slot_out = s;
+  return ODMOE_OK;
+}
+
+int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert) {
+  int rc = check_layer(h, layer);
+  if (rc) return rc;
+  if (!h->pool) return fail(ODMOE_EINVAL, "resident mode: nothing to evict");
+  int s = h->pool->find(layer, expert);
+  if (s < 0) return fail(ODMOE_ESTATE, "expert (%d, %d) holds no slot", layer, expert);
+  h->pool->release(s);
+  return ODMOE_OK;
+}
+
+int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, const float* gate_dev,
+                     const int32_t* idx_host, const void* x_dev, int32_t n_tokens, void* y_dev,
+                     int32_t evict_after) {
+  int rc = check_layer(h, layer);
+  if (rc) return rc;
+  if (n_tokens < 0) return fail(ODMOE_EINVAL, "n_tokens %d < 0", n_tokens);
+  if (n_tokens == 0) return ODMOE_OK;
+  if (!idx_dev || !gate_dev || !x_dev || !y_dev) return fail(ODMOE_EINVAL, "idx/gate/x/y is NULL");
+  const int k = h->cfg.top_k, E = h->cfg.n_experts;
+  const size_t row = (size_t)h->cfg.hidden * h->esize;
+
+  if (!h->pool) {  // resident
+    ExpertSrc src{};
+    src.table = h->table_dev;
+    src.table_off = layer * E;
+    if (n_tokens >= 16 && h->cfg.dtype == ODMOE_BF16) {
+      const size_t need = prefill_workspace_bytes(h->sh, n_tokens);
+      if (need > h->prefill_ws_bytes) {
+        if (h->prefill_ws) HIP_TRY(hipFree(h->prefill_ws));  // hipFree waits for the device
+        h->prefill_ws = nullptr;
+        h->prefill_ws_bytes = 0;
+        hipError_t e = hipMalloc(&h->prefill_ws, need);
+        if (e != hipSuccess) return fail(ODMOE_ENOMEM, "prefill workspace of %zu bytes: %s", need, hipGetErrorString(e));
+        h->prefill_ws_bytes = need;
+      }
+      HIP_TRY(launch_prefill(h->compute, h->sh, h->table_dev, layer * E, idx_dev, gate_dev, x_dev,
+                             n_tokens, y_dev, h->prefill_ws, h->prefill_ws_bytes));
+      return ODMOE_OK;
+    }
+    for (int t = 0; t < n_tokens; ++t) {
+      rc = run_ffn_one_token(h, src, idx_dev + (size_t)t * k, gate_dev + (size_t)t * k,
+                             static_cast<const char*>(x_dev) + t * row, static_cast<char*>(y_dev) + t * row);
+      if (rc) return rc;
+    }
+    return ODMOE_OK;
+  }
+
+  // cacheless
+  if (n_tokens != 1) return fail(ODMOE_EINVAL, "cacheless mode computes one token per call");
+  int32_t ids[ODMOE_MAX_TOPK];
+  if (idx_host) {
+    memcpy(ids, idx_host, k * sizeof(int32_t));
+  } else {
+    HIP_TRY(hipMemcpyAsync(h->idx_pin, idx_dev, k * sizeof(int32_t), hipMemcpyDeviceToHost, h->compute));
+    HIP_TRY(hipStreamSynchronize(h->compute));
+    memcpy(ids, h->idx_pin, k * sizeof(int32_t));
+  }
+  ExpertSrc src{};
+  int32_t slots[ODMOE_MAX_TOPK];
+  for (int i = 0; i < k; ++i) {
+    if (ids[i] < 0 || ids[i] >= E) return fail(ODMOE_EINVAL, "idx[%d] = %d out of range", i, ids[i]);
+    slots[i] = h->pool->find(layer, ids[i]);
+    if (slots[i] < 0)
+      return fail(ODMOE_ESTATE, "expert (%d, %d) is neither loading nor ready", layer, ids[i]);
+    src.slot[i] = h->pool_mem + (size_t)slots[i] * h->expert_bytes;
+  }
+  for (int i = 0; i < k; ++i) HIP_TRY(hipStreamWaitEvent(h->compute, h->ready_ev[slots[i]], 0));
+  rc = run_ffn_one_token(h, src, idx_dev, gate_dev, x_dev, y_dev);
+  if (rc) return rc;
+  for (int i = 0; i < k; ++i) {
+    rc = mark_used(h, slots[i]);
+    if (rc) return rc;
+    if (evict_after) h->pool->release(slots[i]);
+  }
+  return ODMOE_OK;
+}
+
+int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
+                      const int32_t* predicted_idx_host, int32_t* idx_out_host, odmoe_stats* stats) {
+  if (!h) return fail(ODMOE_EINVAL, "handle is NULL");
+  if (!x_dev || !y_dev) return fail(ODMOE_EINVAL, "x/y is NULL");
+  const int L = h->cfg.n_layers, k = h->cfg.top_k, E = h->cfg.n_experts;
+  const bool timed = stats && stats->t_step_ms < 0.f;
+  const auto wall0 = std::chrono::steady_clock::now();
+  if (timed && h->tev.empty()) {
+    h->tev.assign((size_t)5 * L, nullptr);
+    for (auto& e : h->tev) HIP_TRY(hipEventCreate(&e));
+    h->lev.assign((size_t)4 * L * k, nullptr);
+    for (auto& e : h->lev) HIP_TRY(hipEventCreate(&e));
+  }
+  auto TE = [&](int l, int which) -> hipEvent_t { return timed ? h->tev[(size_t)l * 5 + which] : nullptr; };
+  size_t n_lev = 0;  // load events used
+
+  uint64_t n_loads = 0, n_reloads = 0, n_hits = 0;
+  if (h->sched) h->sched->begin_token(predicted_idx_host);
+  std::vector<Action> acts;
+  int rc;
+
+  auto run_actions = [&]() -> int {
+    for (const Action& a : acts) {
+      if (a.kind == Action::LOAD) {
+        hipEvent_t t0 = nullptr, t1 = nullptr;
+        if (timed && n_lev + 2 <= h->lev.size()) {
+          t0 = h->lev[n_lev];
+          t1 = h->lev[n_lev + 1];
+          n_lev += 2;
+        }
+        int r = enqueue_load(h, a.layer, a.expert, a.slot, t0, t1);
+        if (r) return r;
+      }
+      // DROP: the slot was never read by a kernel; the next copy into it is ordered behind
+      // this one on the copy stream.  RELEASE is handled by the caller (needs the event).
+    }
+    acts.clear();
+    return ODMOE_OK;
+  };
+
+  const void* cur = x_dev;
+  for (int l = 0; l < L; ++l) {
+    const bool last = (l == L - 1);
+    int32_t* idx_l = h->idx_dev + (size_t)l * k;
+    float* gate_l = h->gate_dev + (size_t)l * k;
+    if (h->sched) {
+      h->sched->before_route(l, acts);
+      if ((rc = run_actions())) return rc;
+    }
+    if (timed) HIP_TRY(hipEventRecord(TE(l, 0), h->compute));
+    HIP_TRY(launch_route_topk(h->compute, h->sh, h->router_w[l], static_cast<const float*>(h->router_b[l]),
+                              cur, 1, idx_l, gate_l, h->idx_pin_dev + (size_t)l * k));
+
+    ExpertSrc src{};
+    int32_t slots[ODMOE_MAX_TOPK];
+    const int32_t* ids = h->idx_pin + (size_t)l * k;
+    if (h->sched) {
+      // the host has to learn which experts to copy: the one per-layer synchronisation
+      HIP_TRY(hipEventRecord(h->route_ev, h->compute));
+      HIP_TRY(hipEventSynchronize(h->route_ev));
+      for (int i = 0; i < k; ++i)
+        if (ids[i] < 0 || ids[i] >= E) return fail(ODMOE_EHIP, "router produced expert %d", ids[i]);
+      if (!h->sched->after_route(l, ids, acts, slots)) return fail(ODMOE_EBUSY, "no slot for layer %d", l);
+      if ((rc = run_actions())) return rc;
+      for (int i = 0; i < k; ++i) {
+        src.slot[i] = h->pool_mem + (size_t)slots[i] * h->expert_bytes;
+        HIP_TRY(hipStreamWaitEvent(h->compute, h->ready_ev[slots[i]], 0));
+      }
+    } else {
+      src.table = h->table_dev;
+      src.table_off = l * E;
+    }
+
+    void* y_l = (h->cfg.glue == 0) ? (last ? y_dev : h->xbuf[l & 1]) : h->ybuf;
+    if (timed) HIP_TRY(hipEventRecord(TE(l, 1), h->compute));
+    if ((rc = run_ffn_one_token(h, src, idx_l, gate_l, cur, y_l, TE(l, 2)))) return rc;
+    if (timed) HIP_TRY(hipEventRecord(TE(l, 3), h->compute));
+
+    if (h->sched) {
+      h->sched->after_compute(l, ids, acts);
+      for (const Action& a : acts)
+        if (a.kind == Action::RELEASE && (rc = mark_used(h, a.slot))) return rc;
+      acts.clear();
+    }
+    if (h->cfg.glue) {
+      void* x_next = last ? y_dev : h->xbuf[l & 1];
+      HIP_TRY(launch_glue(h->compute, h->sh, cur, y_l, x_next));
+      cur = x_next;
+    } else {
+      cur = y_l;
+    }
+    if (timed) HIP_TRY(hipEventRecord(TE(l, 4), h->compute));
+  }
+  // resident mode with nothing to report stays asynchronous on the compute stream
+  if (h->sched || idx_out_host || stats) HIP_TRY(hipStreamSynchronize(h->compute));
+  if (h->sched) {
+    n_loads = h->sched->loads;
+    n_reloads = h->sched->reloads;
+    n_hits = h->sched->hint_hits;
+  }
+  if (idx_out_host) memcpy(idx_out_host, h->idx_pin, (size_t)L * k * sizeof(int32_t));
+  if (stats) {
+    stats->t_route_ms = stats->t_load_ms = stats->t_ffn_up_ms = stats->t_ffn_down_ms = stats->t_glue_ms = 0.f;
+    if (timed) {
+      if (h->copy) HIP_TRY(hipStreamSynchronize(h->copy));
+      for (int l = 0; l < L; ++l) {
+        float ms = 0.f;
+        // route includes, in cacheless mode, the wait for this layer's expert copies
+        HIP_TRY(hipEventElapsedTime(&ms, TE(l, 0), TE(l, 1)));
+        stats->t_route_ms += ms;
+        HIP_TRY(hipEventElapsedTime(&ms, TE(l, 1), TE(l, 2)));
+        stats->t_ffn_up_ms += ms;
+        HIP_TRY(hipEventElapsedTime(&ms, TE(l, 2), TE(l, 3)));
+        stats->t_ffn_down_ms += ms;
+        HIP_TRY(hipEventElapsedTime(&ms, TE(l, 3), TE(l, 4)));
+        stats->t_glue_ms += ms;
+      }
+      for (size_t i = 0; i < n_lev; i += 2) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, h->lev[i], h->lev[i + 1]));
+        stats->t_load_ms += ms;
+      }
+    }
+    stats->h2d_bytes = n_loads * h->expert_bytes;
+    stats->loads = n_loads;
+    stats->reloads = n_reloads;
+    stats->hint_hits = n_hits;
+    stats->t_step_ms =
+        std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - wall0).count();
+  }
+  return ODMOE_OK;
+}
+
+}  // extern "C"
