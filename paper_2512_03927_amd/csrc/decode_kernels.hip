@@ -52,9 +52,13 @@ __device__ __forceinline__ u32x4 load16(const T* p) {
   return *reinterpret_cast<const u32x4*>(p);
 }
 // Streaming load for weights: each byte is used once, keep it out of the way of reused lines.
+// Expert pointers reach the kernels through a struct or a table, so the compiler cannot tell
+// that they are global addresses; the explicit address-space cast turns what would be flat
+// loads into global loads.
+typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
 template <typename T>
 __device__ __forceinline__ u32x4 load16_stream(const T* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return __builtin_nontemporal_load((global_u32x4_ptr)(p));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -319,6 +323,175 @@ __global__ __launch_bounds__(1024) void glue_kernel(const T* x, const T* y, T* o
   }
 }
 
+// =============================================================================================
+// Register-resident GEMV kernels (the fast path).  The input vector slice a lane multiplies
+// with lives in VGPRs, so the inner loop is nothing but 128-bit streaming loads and FMAs.
+// A partially filled last chunk is handled by zeroing the vector registers of the lanes past
+// the end and clamping their load address (their products are exactly zero).
+// =============================================================================================
+
+// Unpack one 128-bit group of the stored vector into fp32 registers.
+template <typename T>
+__device__ __forceinline__ void load_vec_regs(const T* __restrict__ vec, int v, int nvec, float* out) {
+  constexpr int VEC = DT<T>::VEC;
+  if (v < nvec) {
+    DT<T>::unpack(load16(vec + (size_t)v * VEC), out);
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) out[j] = 0.f;
+  }
+}
+// Same for an fp32 source vector feeding VEC-wide weight groups (the h vector of the w2 GEMV).
+template <int VEC>
+__device__ __forceinline__ void load_f32_regs(const float* __restrict__ vec, int v, int nvec, float* out) {
+  if (v < nvec) {
+#pragma unroll
+    for (int q = 0; q < VEC / 4; ++q) {
+      f32x4 a = *reinterpret_cast<const f32x4*>(vec + (size_t)v * VEC + 4 * q);
+      out[4 * q] = a.x; out[4 * q + 1] = a.y; out[4 * q + 2] = a.z; out[4 * q + 3] = a.w;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) out[j] = 0.f;
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ float dot_group(u32x4 q, const float* v, float acc) {
+  constexpr int VEC = DT<T>::VEC;
+  float f[VEC];
+  DT<T>::unpack(q, f);
+#pragma unroll
+  for (int j = 0; j < VEC; ++j) acc = fmaf(f[j], v[j], acc);
+  return acc;
+}
+
+// h[i, j] = silu(W1_i[j,:] . x) * (W3_i[j,:] . x).  x in registers (NCH chunks of 64*VEC
+// elements); every wave owns `rpw` consecutive (expert rank, row) pairs, i.e. one long
+// contiguous run of W1 and one of W3.  FULL: H is exactly NCH chunks (constant load offsets).
+template <typename T, int NCH, bool FULL>
+__global__ __launch_bounds__(256) void ffn_up_reg_kernel(ExpertSrc src, const int32_t* __restrict__ idx,
+                                                          const T* __restrict__ x,
+                                                          float* __restrict__ hbuf, int H, int F, int k,
+                                                          int rpw) {
+  constexpr int VEC = DT<T>::VEC;
+  constexpr int CHUNK = WAVE * VEC;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int nvec = H / VEC;
+  float xr[NCH][VEC];
+  int off[NCH];  // element offset of this lane's group in chunk c (clamped into the row)
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int v = c * WAVE + lane;
+    load_vec_regs<T>(x, v, nvec, xr[c]);
+    off[c] = FULL ? c * CHUNK + lane * VEC : (v < nvec ? v : nvec - 1) * VEC;
+  }
+  const int total = k * F;
+  const int r_begin = (blockIdx.x * nw + wave) * rpw;
+  const int r_end = (r_begin + rpw < total) ? r_begin + rpw : total;
+  int r = r_begin;
+  while (r < r_end) {
+    const int i = r / F;
+    const int j0 = r - i * F;
+    const int seg_end = ((i + 1) * F < r_end) ? (i + 1) * F : r_end;
+    const int nrow = seg_end - r;
+    const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
+    float* hout = hbuf + (size_t)i * F + j0;
+#pragma unroll 1
+    for (int rr = 0; rr < nrow; ++rr) {
+      const T* w1 = base + (size_t)(j0 + rr) * H;
+      const T* w3 = w1 + (size_t)F * H;
+      u32x4 qa[NCH], qb[NCH];
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        if constexpr (FULL) {
+          qa[c] = load16_stream(w1 + lane * VEC + c * CHUNK);
+          qb[c] = load16_stream(w3 + lane * VEC + c * CHUNK);
+        } else {
+          qa[c] = load16_stream(w1 + off[c]);
+          qb[c] = load16_stream(w3 + off[c]);
+        }
+      }
+      float a = 0.f, b = 0.f;
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        a = dot_group<T>(qa[c], xr[c], a);
+        b = dot_group<T>(qb[c], xr[c], b);
+      }
+      a = wave_sum(a);
+      b = wave_sum(b);
+      if (lane == 0) hout[rr] = a / (1.f + expf(-a)) * b;
+    }
+    r = seg_end;
+  }
+}
+
+// y[r] = sum_i gate[i] * (W2_i[r,:] . h_i).  The block owns `rpb` output rows.  Its waves form
+// a grid of nwc column slices x n_eg expert groups: a wave owns CPW consecutive column chunks of
+// the experts of its group and keeps that slice of h_i in registers; two rows are in flight per
+// wave.  Per-wave partial sums meet in LDS and are added in wave order: no atomics, fixed order.
+template <typename T, int CPW>
+__global__ __launch_bounds__(CPW <= 4 ? 1024 : 512) void ffn_down_reg_kernel(ExpertSrc src, const int32_t* __restrict__ idx,
+                                                             const float* __restrict__ gate,
+                                                             const float* __restrict__ hbuf,
+                                                             T* __restrict__ y, int H, int F, int k,
+                                                             int rpb, int nwc) {
+  constexpr int VEC = DT<T>::VEC;
+  constexpr int RIF = 2;  // rows in flight
+  extern __shared__ float part[];  // [nw][rpb]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const int cw = wave % nwc;   // which column slice this wave owns
+  const int eg = wave / nwc;   // which expert group (experts eg, eg + n_eg, ...)
+  const int n_eg = nw / nwc;
+  const int nvec = F / VEC;
+  const int r0 = blockIdx.x * rpb;
+  float* mypart = part + wave * rpb;
+  if (lane == 0)
+    for (int t = 0; t < rpb; ++t) mypart[t] = 0.f;
+  int off[CPW];
+#pragma unroll
+  for (int c = 0; c < CPW; ++c) {
+    const int v = (cw * CPW + c) * WAVE + lane;
+    off[c] = (v < nvec ? v : nvec - 1) * VEC;
+  }
+  for (int i = eg; i < k; i += n_eg) {
+    const float g = gate[i];
+    const T* w2 = static_cast<const T*>(expert_ptr(src, idx, i)) + (size_t)2 * F * H;
+    const float* hv = hbuf + (size_t)i * F;
+    float hr[CPW][VEC];
+#pragma unroll
+    for (int c = 0; c < CPW; ++c) load_f32_regs<VEC>(hv, (cw * CPW + c) * WAVE + lane, nvec, hr[c]);
+#pragma unroll 1
+    for (int rr = 0; rr < rpb; rr += RIF) {
+      u32x4 q[RIF][CPW];
+#pragma unroll
+      for (int u = 0; u < RIF; ++u) {
+        int row = r0 + rr + u;
+        row = row < H ? row : H - 1;
+        const T* p = w2 + (size_t)row * F;
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) q[u][c] = load16_stream(p + off[c]);
+      }
+#pragma unroll
+      for (int u = 0; u < RIF; ++u) {
+        float d = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) d = dot_group<T>(q[u][c], hr[c], d);
+        d = wave_sum(d);
+        if (lane == 0 && rr + u < rpb) mypart[rr + u] = fmaf(g, d, mypart[rr + u]);
+      }
+    }
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < rpb; t += blockDim.x) {
+    if (r0 + t < H) {
+      float sum = 0.f;
+      for (int w = 0; w < nw; ++w) sum += part[w * rpb + t];
+      y[r0 + t] = DT<T>::from_f32(sum);
+    }
+  }
+}
+
 inline size_t lds_vec_bytes(int n, int vec) {
   const int chunk = WAVE * vec;
   return (size_t)((n + chunk - 1) / chunk) * chunk * sizeof(float);
@@ -362,40 +535,156 @@ hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, con
   return hipGetLastError();
 }
 
+namespace {
+
+// Launch-shape overrides for tuning experiments (0 = use the built-in policy).
+int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0;
+
+int g_num_cu = 0;
+int num_cu() {
+  if (g_num_cu == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      g_num_cu = n;
+    else
+      g_num_cu = 256;
+  }
+  return g_num_cu;
+}
+
+template <typename T, int NCH>
+hipError_t launch_up_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                           const void* x, float* hbuf) {
+  const int nw = 4;
+  const long total = (long)sh.k * sh.F;
+  // one block per CU when the rows allow it: every wave streams one long contiguous run
+  long rpw = (total + (long)num_cu() * nw - 1) / ((long)num_cu() * nw);
+  // small layers are latency bound: spread them over four times as many waves
+  if (rpw < 16) rpw = (total + (long)num_cu() * nw * 4 - 1) / ((long)num_cu() * nw * 4);
+  if (rpw < 1) rpw = 1;
+  if (g_tune_up_rpw > 0) rpw = g_tune_up_rpw;
+  const int grid = (int)((total + nw * rpw - 1) / (nw * rpw));
+  if (sh.H == NCH * WAVE * DT<T>::VEC)
+    ffn_up_reg_kernel<T, NCH, true><<<grid, nw * WAVE, 0, s>>>(src, idx, static_cast<const T*>(x), hbuf,
+                                                                sh.H, sh.F, sh.k, (int)rpw);
+  else
+    ffn_up_reg_kernel<T, NCH, false><<<grid, nw * WAVE, 0, s>>>(src, idx, static_cast<const T*>(x), hbuf,
+                                                                 sh.H, sh.F, sh.k, (int)rpw);
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_up_reg(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                         const void* x, float* hbuf, int nch) {
+  switch (nch) {
+#define ODMOE_CASE(N) case N: return launch_up_reg_n<T, N>(s, sh, src, idx, x, hbuf);
+    ODMOE_CASE(1) ODMOE_CASE(2) ODMOE_CASE(3) ODMOE_CASE(4) ODMOE_CASE(5) ODMOE_CASE(6)
+    ODMOE_CASE(7) ODMOE_CASE(8) ODMOE_CASE(9) ODMOE_CASE(10) ODMOE_CASE(11) ODMOE_CASE(12)
+    ODMOE_CASE(13) ODMOE_CASE(14) ODMOE_CASE(15) ODMOE_CASE(16)
+#undef ODMOE_CASE
+  }
+  return hipErrorInvalidValue;
+}
+
+template <typename T, int CPW>
+hipError_t launch_down_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                             const float* gate, const float* hbuf, void* y, int nwb) {
+  // expert groups: waves left over in a block (up to 8 when slices are short) take different experts
+  const int max_waves = CPW <= 4 ? 16 : 8;
+  int n_eg = 1;
+  if (nwb <= 2) n_eg = sh.k < max_waves / nwb ? sh.k : max_waves / nwb;
+  if (n_eg > 8) n_eg = 8;
+  if (g_tune_down_eg > 0) n_eg = g_tune_down_eg;
+  int rpb = (sh.H + num_cu() - 1) / num_cu();
+  if (n_eg > 1 && rpb > 4) rpb = 4;  // small layers: more, shorter blocks
+  rpb = (rpb + 1) & ~1;              // two rows in flight
+  if (rpb > 64) rpb = 64;
+  if (g_tune_down_rpb > 0) rpb = g_tune_down_rpb;
+  const int grid = (sh.H + rpb - 1) / rpb;
+  const int nw = nwb * n_eg;
+  const size_t lds = (size_t)nw * rpb * sizeof(float);
+  ffn_down_reg_kernel<T, CPW><<<grid, nw * WAVE, lds, s>>>(src, idx, gate, hbuf, static_cast<T*>(y),
+                                                           sh.H, sh.F, sh.k, rpb, nwb);
+  return hipGetLastError();
+}
+
+// Split of the NC column chunks of a w2 row over the waves of a block: CPW chunks per wave.
+// Up to 4 chunks per wave (blocks of up to 16 waves) with the least padding, ties going to
+// more chunks per wave; rows too long for that take 5..8 chunks per wave (up to 8 waves).
+inline bool pick_down_split(int nc, int* cpw_out, int* nwb_out) {
+  int best_cpw = 0, best_waste = 1 << 30;
+  for (int cpw = 1; cpw <= 4; ++cpw) {
+    const int nwb = (nc + cpw - 1) / cpw;
+    if (nwb > 16) continue;
+    const int waste = nwb * cpw - nc;
+    if (waste <= best_waste) { best_waste = waste; best_cpw = cpw; }
+  }
+  for (int cpw = 5; cpw <= 8 && !best_cpw; ++cpw)
+    if ((nc + cpw - 1) / cpw <= 8) best_cpw = cpw;
+  if (!best_cpw) return false;
+  *cpw_out = best_cpw;
+  *nwb_out = (nc + best_cpw - 1) / best_cpw;
+  return true;
+}
+
+template <typename T>
+hipError_t launch_down_reg(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                           const float* gate, const float* hbuf, void* y, int cpw, int nwb) {
+  switch (cpw) {
+#define ODMOE_CASE(N) case N: return launch_down_reg_n<T, N>(s, sh, src, idx, gate, hbuf, y, nwb);
+    ODMOE_CASE(1) ODMOE_CASE(2) ODMOE_CASE(3) ODMOE_CASE(4) ODMOE_CASE(5) ODMOE_CASE(6)
+    ODMOE_CASE(7) ODMOE_CASE(8)
+#undef ODMOE_CASE
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
 hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
                          const void* x, float* hbuf) {
+  const int vec = sh.dtype == ODMOE_F32 ? 4 : 8;
+  const int nch = (sh.H + WAVE * vec - 1) / (WAVE * vec);
+  if (nch <= 16) {
+    return sh.dtype == ODMOE_F32 ? launch_up_reg<float>(s, sh, src, idx, x, hbuf, nch)
+                                 : launch_up_reg<bf16_t>(s, sh, src, idx, x, hbuf, nch);
+  }
+  // generic fallback: x staged in LDS
   const int nw = UP_THREADS / WAVE;
   const long total = (long)sh.k * sh.F;
   const int grid = (int)((total + nw * UP_RPW - 1) / (nw * UP_RPW));
-  if (sh.dtype == ODMOE_F32) {
-    const size_t lds = lds_vec_bytes(sh.H, 4);
-    if (lds > MAX_LDS) return hipErrorInvalidValue;
+  const size_t lds = lds_vec_bytes(sh.H, vec);
+  if (lds > MAX_LDS) return hipErrorInvalidValue;
+  if (sh.dtype == ODMOE_F32)
     ffn_up_kernel<float, UP_RPW><<<grid, UP_THREADS, lds, s>>>(src, idx, static_cast<const float*>(x),
                                                                hbuf, sh.H, sh.F, sh.k);
-  } else {
-    const size_t lds = lds_vec_bytes(sh.H, 8);
-    if (lds > MAX_LDS) return hipErrorInvalidValue;
+  else
     ffn_up_kernel<bf16_t, UP_RPW><<<grid, UP_THREADS, lds, s>>>(src, idx, static_cast<const bf16_t*>(x),
                                                                 hbuf, sh.H, sh.F, sh.k);
-  }
   return hipGetLastError();
 }
 
 hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
                            const int32_t* idx, const float* gate, const float* hbuf, void* y) {
+  const int vec = sh.dtype == ODMOE_F32 ? 4 : 8;
+  const int nc = (sh.F + WAVE * vec - 1) / (WAVE * vec);
+  int cpw = 0, nwb = 0;
+  if (pick_down_split(nc, &cpw, &nwb)) {
+    return sh.dtype == ODMOE_F32 ? launch_down_reg<float>(s, sh, src, idx, gate, hbuf, y, cpw, nwb)
+                                 : launch_down_reg<bf16_t>(s, sh, src, idx, gate, hbuf, y, cpw, nwb);
+  }
+  // generic fallback: h staged in LDS, one expert at a time
   const int nw = DOWN_THREADS / WAVE;
   const int grid = (sh.H + nw * DOWN_RPW - 1) / (nw * DOWN_RPW);
-  if (sh.dtype == ODMOE_F32) {
-    const size_t lds = lds_vec_bytes(sh.F, 4);
-    if (lds > MAX_LDS) return hipErrorInvalidValue;
+  const size_t lds = lds_vec_bytes(sh.F, vec);
+  if (lds > MAX_LDS) return hipErrorInvalidValue;
+  if (sh.dtype == ODMOE_F32)
     ffn_down_kernel<float, DOWN_RPW><<<grid, DOWN_THREADS, lds, s>>>(
         src, idx, gate, hbuf, static_cast<float*>(y), sh.H, sh.F, sh.k);
-  } else {
-    const size_t lds = lds_vec_bytes(sh.F, 8);
-    if (lds > MAX_LDS) return hipErrorInvalidValue;
+  else
     ffn_down_kernel<bf16_t, DOWN_RPW><<<grid, DOWN_THREADS, lds, s>>>(
         src, idx, gate, hbuf, static_cast<bf16_t*>(y), sh.H, sh.F, sh.k);
-  }
   return hipGetLastError();
 }
 

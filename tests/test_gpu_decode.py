@@ -73,12 +73,17 @@ SHAPES = [
     (8, 8, 2, 1, "bf16"),           # smallest legal shape, k = 1 (gate == 1)
     (2048, 1408, 64, 6, "bf16"),    # fine-grained layer shape (config 5)
     (64, 72, 8, 8, "f32"),          # k = E = max top-k
+    (4104, 264, 4, 2, "f32"),       # H beyond the register-resident w1/w3 kernel -> LDS-staged fallback
+    (64, 32776, 3, 2, "f32"),       # F beyond the register-resident w2 kernel -> LDS-staged fallback
+    (8200, 72, 4, 2, "bf16"),       # bf16 H just past 16 chunks -> fallback
+    (4096, 14336, 8, 2, "bf16"),    # the Mixtral layer shape (configs 2-4)
 ]
 
 
 @pytest.mark.parametrize("Hd,F,E,k,dtype", SHAPES)
 def test_layer_parity_shapes(H, Hd, F, E, k, dtype):
-    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=5, router_bias=(E == 5), seed=3)
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=5 if Hd * F < (1 << 24) else 2,
+                          router_bias=(E == 5), seed=3)
     Wg, b, experts = synth.layer_weights(cfg)
     X = synth.tokens(cfg)
     Y, IDX, G = oracle_tokens(cfg, X, Wg, b, experts)
