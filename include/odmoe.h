@@ -137,8 +137,10 @@ int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert);
  *   idx_host   optional host copy of idx (cacheless mode needs to know the experts on the
  *              host; when NULL there, the library reads idx_dev back and blocks for it).
  *   n_tokens   < 16: one fused w1/w3+SiLU GEMV and one w2+combine GEMV per token;
- *              >= 16 (bf16, resident): prefill path of Section 3.3 -- tokens are grouped by
- *              expert and each expert runs a grouped GEMM on the matrix cores.
+ *              >= 16 (resident, bf16, hidden and ffn multiples of 64): prefill path of
+ *              Section 3.3 -- tokens are grouped by expert and each expert runs a grouped GEMM
+ *              on the matrix cores; the SwiGLU intermediate is rounded to bf16 there (the
+ *              matrix cores take bf16 operands).  Other shapes fall back to the per-token path.
  *   evict_after  cacheless mode: nonzero releases the experts' slots after the kernels that
  *              read them (the paper's prompt eviction).  Ignored in resident mode.
  * Cacheless mode supports n_tokens == 1 here.  The compute stream waits (stream side) for

@@ -41,6 +41,7 @@ hipError_t launch_glue(hipStream_t s, const Shape& sh, const void* x, const void
 
 // Prefill (bf16, resident): tokens grouped by expert, grouped GEMMs on the matrix cores.
 // Workspace sizes in bytes for T tokens; the workspace is carved by the launcher.
+bool prefill_supported(const Shape& sh);  // bf16 and H, F multiples of 64
 size_t prefill_workspace_bytes(const Shape& sh, int32_t T);
 hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* table,
                           int32_t table_off, const int32_t* idx, const float* gate, const void* x,

@@ -335,7 +335,7 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
     ExpertSrc src{};
     src.table = h->table_dev;
     src.table_off = layer * E;
-    if (n_tokens >= 16 && h->cfg.dtype == ODMOE_BF16) {
+    if (n_tokens >= 16 && prefill_supported(h->sh)) {
       const size_t need = prefill_workspace_bytes(h->sh, n_tokens);
       if (need > h->prefill_ws_bytes) {
         if (h->prefill_ws) HIP_TRY(hipFree(h->prefill_ws));  // hipFree waits for the device
