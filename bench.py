@@ -44,6 +44,7 @@ def main() -> int:
     ap.add_argument("--cacheless-tokens", type=int, default=3,
                     help="tokens of the 32-layer cacheless stack to time (0 = skip)")
     ap.add_argument("--cpu-tokens", type=int, default=3, help="tokens the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--prefill-iters", type=int, default=5, help="timed prefill calls of 512 tokens (0 = skip)")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -124,6 +125,44 @@ def main() -> int:
     Y_keep = harness.from_device(Y[:4]).copy()
     stack.close()
 
+    # ---- prefill: 512 tokens in one call, skewed routing, grouped GEMM on the matrix cores
+    prefill = None
+    if args.prefill_iters > 0:
+        c4 = synth.CONFIGS[4]
+        Wg4, _, experts4 = layer
+        b4 = synth.router_bias(c4)
+        X4 = harness.to_device(synth.tokens(c4))
+        with harness.MoEStack(c4, [(Wg4, b4, experts4)]) as st4:
+            idx4, gate4 = st4.route(0, X4)
+            Y4 = torch.empty_like(X4)
+            counts = np.bincount(idx4.cpu().numpy().ravel(), minlength=c4.n_experts)
+
+            def prefill_once():
+                B.odmoe_route_topk(st4.handle, 0, X4, c4.n_tokens, idx4, gate4)
+                B.odmoe_expert_ffn(st4.handle, 0, idx4, gate4, None, X4, c4.n_tokens, Y4, 0)
+
+            prefill_once()
+            torch.cuda.synchronize()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for _ in range(args.prefill_iters):
+                prefill_once()
+            ev1.record()
+            torch.cuda.synchronize()
+            ms = ev0.elapsed_time(ev1) / args.prefill_iters
+        flops = 6.0 * c4.n_tokens * c4.top_k * c4.hidden * c4.ffn
+        wbytes = float(np.count_nonzero(counts)) * c4.expert_bytes
+        # per-expert bound: weights once from HBM vs that expert's GEMM flops on the matrix cores
+        ideal_ms = sum(max(c4.expert_bytes / (HBM_PEAK_GBPS * 1e9),
+                           6.0 * n * c4.hidden * c4.ffn / 2.5e15) for n in counts if n > 0) * 1e3
+        prefill = {"workload": c4.name, "tokens": c4.n_tokens, "ms": round(ms, 4),
+                   "tokens_per_s": round(c4.n_tokens / (ms * 1e-3), 1),
+                   "tflops": round(flops / (ms * 1e-3) / 1e12, 1), "mfma_frac_of_2500": round(flops / (ms * 1e-3) / 2.5e15, 4),
+                   "weight_GBps": round(wbytes / (ms * 1e-3) / 1e9, 1),
+                   "roofline_ms_sum_max_hbm_mfma": round(ideal_ms, 4), "frac_of_roofline": round(ideal_ms / ms, 4),
+                   "tokens_per_expert": counts.tolist()}
+        log(f"[bench] prefill: {prefill}")
+
     # ---- cacheless 32-layer stack, short run (host-link roofline)
     cacheless = None
     if args.cacheless_tokens > 0:
@@ -190,7 +229,7 @@ def main() -> int:
                    "top_k": cfg.top_k, "n_layers": 1, "tokens_per_step": T, "batch": 1,
                    "weights": "resident in HBM"},
         "expert_gemv_hbm_GBps": None if gemv_gbps is None else round(gemv_gbps, 1),
-        "roofline": roofline, "cacheless": cacheless, "cpu_baseline": cpu,
+        "roofline": roofline, "cacheless": cacheless, "prefill": prefill, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
     return 0

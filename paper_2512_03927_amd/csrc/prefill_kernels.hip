@@ -15,10 +15,13 @@
 namespace odmoe {
 namespace {
 
-constexpr int BM = 128;  // token rows per block tile
-constexpr int BN = 64;   // weight rows per block tile (per matrix)
-constexpr int BK = 64;   // K elements per pipeline step (128 bytes per row)
-constexpr int GEMM_THREADS = 256;
+constexpr int BMX = 256;     // most rows of one expert a block takes (one "chunk")
+constexpr int BN = 128;      // weight rows per block tile: two 64-row halves (W1 and W3 rows of the
+                             // same 64 ffn columns for the first GEMM, 128 consecutive rows for the second)
+constexpr int BK = 64;       // K elements per pipeline step (one 128-byte line per row)
+constexpr int GEMM_THREADS = 512;
+constexpr int MAX_KSPLIT = 8;
+constexpr size_t GEMM_LDS = 144 * 1024;  // the LDS ring; its depth depends on the rows of the chunk
 
 typedef uint16_t bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -36,7 +39,8 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 // ---------------------------------------------------------------------------------------------
 // Bucket the n = T*k token-slots by expert.  One block.  Slots with an out-of-range expert id
 // are left out (inv = -1) and contribute nothing.
-// tiles: (expert, first row within the expert) pairs of BM rows each; *n_tiles their number.
+// tiles: (expert, first row within the expert, rows) triples, at most BMX rows each, the rows of
+// an expert split evenly over its chunks; *n_tiles their number.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restrict__ idx, int n, int E,
                                                            int32_t* __restrict__ offsets,
@@ -58,9 +62,12 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
     for (int e = 0; e < E; ++e) {
       start[e] = run;
       offsets[e] = run;
-      for (int m0 = 0; m0 < cnt[e]; m0 += BM) {
-        tiles[2 * nt] = e;
-        tiles[2 * nt + 1] = m0;
+      const int nch = (cnt[e] + BMX - 1) / BMX;
+      const int per = nch ? (((cnt[e] + nch - 1) / nch + 31) & ~31) : 0;
+      for (int m0 = 0; m0 < cnt[e]; m0 += per) {
+        tiles[3 * nt] = e;
+        tiles[3 * nt + 1] = m0;
+        tiles[3 * nt + 2] = (cnt[e] - m0 < per) ? cnt[e] - m0 : per;
         ++nt;
       }
       run += cnt[e];
@@ -85,148 +92,214 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
-// Grouped GEMM.  Block tile BM x BN (x2 matrices when DUAL), K pipelined in steps of BK through
-// double-buffered LDS; 4 waves as 2 (M) x 2 (N), each wave 64 x 32 outputs per matrix.
-// LDS rows are 128 bytes; the 16-byte piece p of row r sits at slot p ^ (r & 7), which makes
-// both the staging stores and the MFMA fragment reads conflict-free.
-//   DUAL  : B0 = W1 rows, B1 = W3 rows; out = bf16( silu(A B0^T) * (A B1^T) )
-//   !DUAL : out = fp32( A B0^T )
-// blockIdx.x = N tile, blockIdx.y = entry of the M-tile list (blocks past *n_tiles exit).
+// Grouped GEMM  C[p, n] = sum_k A[row(p), k] * W_e[n, k]  for one chunk (up to BMX = 256 rows) of
+// one expert e and BN = 128 weight rows.  Built around the weight stream, which is what bounds it:
+//   - one block takes all rows of the chunk, so an expert with up to 256 tokens reads its weights
+//     exactly once;
+//   - global memory goes straight into LDS (global_load_lds_dwordx4: a wave fills 1 KB = 8 rows of
+//     128 bytes per instruction, every 128-byte line fully coalesced) in a ring of K-steps of
+//     BK = 64; no staging registers, one s_barrier per step, and the only vmcnt wait is for the
+//     step about to be used.  The ring is as deep as 144 KB of LDS allow for the chunk's rows:
+//     6 steps for up to 64 rows, 4 for up to 128, 3 for up to 256 - small chunks do little
+//     arithmetic per step, so they need more weight bytes in flight to cover HBM latency;
+//   - LDS rows are 128 bytes; the 16-byte piece q of row r sits at slot q ^ (r & 7) (the lane
+//     that fills slot s of row r fetches piece s ^ (r & 7)), so the MFMA fragment reads are
+//     conflict-free;
+//   - 8 waves as 4 (M, 64 rows) x 2 (N, 32 columns of each 64-row half); 32-row tiles past the
+//     end of the chunk are skipped.
+//   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+63; out = bf16( silu(A W1^T) * (A W3^T) )
+//   !SILU : halves = weight rows n0..n0+63 / n0+64..n0+127; out = fp32 partial sums for K range
+//           blockIdx.z, [gridDim.z][rows, ldo]
+// grid: x = entry of the chunk list, y = N tile, z = K split.  K is a multiple of 64.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_slot(int row, int piece) { return row * BK + ((piece ^ (row & 7)) << 3); }
 
-template <bool DUAL>
-__global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(
-    const bf16_t* __restrict__ A, int lda, const int32_t* __restrict__ a_slot, int slot_div,
-    const void* const* __restrict__ table, int table_off, size_t b0_off, size_t b1_off,
-    const int32_t* __restrict__ offsets, const int32_t* __restrict__ tiles,
-    const int32_t* __restrict__ n_tiles, void* __restrict__ out, int ldo, int N, int K) {
-  constexpr int NB = DUAL ? 2 : 1;
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  bf16_t* As = smem;                       // [2][BM*BK]
-  bf16_t* Bs = smem + 2 * BM * BK;         // [2][NB][BN*BK]
+// s_waitcnt vmcnt(N) only (other counters left at their maximum).
+#define ODMOE_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
-  if ((int)blockIdx.y >= *n_tiles) return;
-  const int e = tiles[2 * blockIdx.y];
-  const int row_lo = offsets[e] + tiles[2 * blockIdx.y + 1];
-  const int row_end = offsets[e + 1];
-  const int n0 = blockIdx.x * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+typedef const __attribute__((address_space(1))) void* global_void_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+struct GemmArgs {
+  const bf16_t* A;            // activations [rows, lda]
+  int lda;
+  const int32_t* a_slot;      // sorted position -> token-slot (row of A = slot / slot_div), or null
+  int slot_div;
+  const void* const* table;   // expert base pointers
+  int table_off;
+  size_t b_off[2];            // element offsets of the two 64-row halves' matrix starts
+  int b_row[2];               // first weight row of each half relative to n0
+  const int32_t* offsets;
+  const int32_t* tiles;
+  const int32_t* n_tiles;
+  void* out;
+  int ldo, N, K, k_per_split;
+  size_t split_stride;
+};
+
+template <bool SILU, int A_INSTR, int NSTAGE>
+__device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int e, int row_lo, int nrows) {
+  constexpr int A_ROWS = 64 * A_INSTR;
+  constexpr int LPS = A_INSTR + 2;                      // DMA loads per wave per K-step
+  constexpr size_t A_STAGE = (size_t)A_ROWS * BK;
+  constexpr size_t STAGE = A_STAGE + (size_t)BN * BK;
+  static_assert(NSTAGE * STAGE * sizeof(bf16_t) <= GEMM_LDS, "ring does not fit");
+  static_assert((NSTAGE - 2) * LPS < 64, "vmcnt is 6 bits");
+
+  const int n0 = blockIdx.y * (SILU ? BN / 2 : BN);
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
+  const int K = g.K;
+  const int k_begin = blockIdx.z * g.k_per_split;
+  const int k_end = (k_begin + g.k_per_split < K) ? k_begin + g.k_per_split : K;
+  if (k_begin >= k_end) return;
+  const int nk = (k_end - k_begin) / BK;
 
-  // ---- staging assignment: thread -> (row tid/8 + 32 j, 16-byte piece tid%8)
-  const int st_row = tid >> 3, st_piece = tid & 7;
-  const bf16_t* a_src[BM / 32];
+  // ---- what this lane fetches: row (lane >> 3) of each 8-row group, piece (lane & 7) ^ (lane >> 3)
+  const int sub = lane >> 3;
+  const int piece = (lane & 7) ^ sub;
+  const bf16_t* a_src[A_INSTR];
 #pragma unroll
-  for (int j = 0; j < BM / 32; ++j) {
-    int p = row_lo + st_row + 32 * j;
-    p = p < row_end ? p : row_end - 1;                 // rows past the group: any valid row
-    const int src_row = a_slot ? a_slot[p] / slot_div : p;
-    a_src[j] = A + (size_t)src_row * lda + st_piece * 8;
+  for (int i = 0; i < A_INSTR; ++i) {
+    int r = (i * 8 + wave) * 8 + sub;
+    r = r < nrows ? r : nrows - 1;                      // rows past the chunk: repeat its last row
+    const int p = row_lo + r;
+    const int src_row = g.a_slot ? g.a_slot[p] / g.slot_div : p;
+    a_src[i] = g.A + (size_t)src_row * g.lda + k_begin + piece * 8;
   }
-  const bf16_t* wbase = static_cast<const bf16_t*>(table[table_off + e]);
-  const bf16_t* b_src[NB][BN / 32];
+  const bf16_t* wbase = static_cast<const bf16_t*>(g.table[g.table_off + e]);
+  const bf16_t* b_src[2];
 #pragma unroll
-  for (int j = 0; j < BN / 32; ++j) {
-    int n = n0 + st_row + 32 * j;
-    n = n < N ? n : N - 1;
-    b_src[0][j] = wbase + b0_off + (size_t)n * K + st_piece * 8;
-    if constexpr (DUAL) b_src[1][j] = wbase + b1_off + (size_t)n * K + st_piece * 8;
+  for (int b = 0; b < 2; ++b) {
+    int n = n0 + g.b_row[b] + wave * 8 + sub;
+    n = n < g.N ? n : g.N - 1;                          // rows past N: any valid row (never stored)
+    b_src[b] = wbase + g.b_off[b] + (size_t)n * K + k_begin + piece * 8;
   }
-
-  u32x4 ra[BM / 32], rb[NB][BN / 32];
-  auto load_tile = [&](int kt) {
+  auto issue = [&](int stage, int kt) {
+    bf16_t* sa = smem + stage * STAGE;
     const int ko = kt * BK;
 #pragma unroll
-    for (int j = 0; j < BM / 32; ++j) ra[j] = *reinterpret_cast<const u32x4*>(a_src[j] + ko);
+    for (int i = 0; i < A_INSTR; ++i)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(a_src[i] + ko),
+                                       (lds_void_ptr)(sa + (i * 8 + wave) * 8 * BK), 16, 0, 0);
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-      for (int j = 0; j < BN / 32; ++j)
-        rb[b][j] = __builtin_nontemporal_load((global_u32x4_ptr)(b_src[b][j] + ko));
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < BM / 32; ++j)
-      *reinterpret_cast<u32x4*>(As + buf * BM * BK + lds_slot(st_row + 32 * j, st_piece)) = ra[j];
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-      for (int j = 0; j < BN / 32; ++j)
-        *reinterpret_cast<u32x4*>(Bs + (buf * NB + b) * BN * BK + lds_slot(st_row + 32 * j, st_piece)) = rb[b][j];
+    for (int b = 0; b < 2; ++b)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(b_src[b] + ko),
+                                       (lds_void_ptr)(sa + A_STAGE + (b * 64 + wave * 8) * BK), 16, 0, 0);
   };
 
-  f32x16 acc[2][NB];
+  f32x16 acc[2][2];
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-    for (int b = 0; b < NB; ++b)
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][b][i] = 0.f;
 
-  const int nk = K / BK;
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-  const int fr = lane & 31, fg = lane >> 5;  // fragment row within a 32-tile, K half
+  const int fr = lane & 31, fg = lane >> 5;            // fragment row within a 32-tile, K half
+  const bool mt_on[2] = {wm * 64 < nrows, wm * 64 + 32 < nrows};
+
+  const int last = nk - 1;
+#pragma unroll
+  for (int st = 0; st < NSTAGE - 1; ++st) issue(st, st < last ? st : last);
+  int stage = 0, refill = NSTAGE - 1;
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_tile(kt + 1);
-    const bf16_t* as = As + buf * BM * BK;
+    ODMOE_VMCNT((NSTAGE - 2) * LPS);   // this wave's fills of step kt have landed (later steps may fly)
+    __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done with step kt-1
+    const int nxt = kt + NSTAGE - 1;
+    issue(refill, nxt < last ? nxt : last);            // refill the buffer that step kt-1 used
+    if (mt_on[0]) {
+      const bf16_t* sa = smem + stage * STAGE;
+      const bf16_t* sb = sa + A_STAGE;
 #pragma unroll
-    for (int s = 0; s < BK / 16; ++s) {
-      const int piece = 2 * s + fg;
-      bf16x8 af[2], bfrag[NB];
+      for (int s = 0; s < BK / 16; ++s) {
+        const int pc = 2 * s + fg;
+        bf16x8 bfrag[2];
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-        af[mt] = *reinterpret_cast<const bf16x8*>(as + lds_slot(wm * 64 + mt * 32 + fr, piece));
+        for (int b = 0; b < 2; ++b)
+          bfrag[b] = *reinterpret_cast<const bf16x8*>(sb + lds_slot(b * 64 + wn * 32 + fr, pc));
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(sa + lds_slot(wm * 64 + fr, pc));
 #pragma unroll
-      for (int b = 0; b < NB; ++b)
-        bfrag[b] = *reinterpret_cast<const bf16x8*>(Bs + (buf * NB + b) * BN * BK + lds_slot(wn * 32 + fr, piece));
+        for (int b = 0; b < 2; ++b)
+          acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag[b], acc[0][b], 0, 0, 0);
+        if (mt_on[1]) {
+          const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(sa + lds_slot(wm * 64 + 32 + fr, pc));
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-          acc[mt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mt], bfrag[b], acc[mt][b], 0, 0, 0);
+          for (int b = 0; b < 2; ++b)
+            acc[1][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfrag[b], acc[1][b], 0, 0, 0);
+        }
+      }
     }
-    if (kt + 1 < nk) store_tile(buf ^ 1);
-    __syncthreads();
+    stage = stage + 1 == NSTAGE ? 0 : stage + 1;
+    refill = refill + 1 == NSTAGE ? 0 : refill + 1;
   }
+  ODMOE_VMCNT(0);  // no fill may still be on its way into LDS when the block retires
 
   // ---- epilogue.  Accumulator layout: column = lane % 32, row = (i/4)*8 + (lane/32)*4 + i%4.
-  const int col = n0 + wn * 32 + fr;
-  if (col >= N) return;
 #pragma unroll
   for (int mt = 0; mt < 2; ++mt) {
+    if (!mt_on[mt]) continue;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int m = (i >> 2) * 8 + fg * 4 + (i & 3);
-      const int p = row_lo + wm * 64 + mt * 32 + m;
-      if (p < row_end) {
-        if constexpr (DUAL) {
-          const float a = acc[mt][0][i], b = acc[mt][1][i];
-          static_cast<bf16_t*>(out)[(size_t)p * ldo + col] = f32_to_bf16(a / (1.f + expf(-a)) * b);
+      const int m = wm * 64 + mt * 32 + (i >> 2) * 8 + fg * 4 + (i & 3);
+      if (m < nrows) {
+        const size_t p = (size_t)(row_lo + m);
+        if constexpr (SILU) {
+          const int col = n0 + wn * 32 + fr;
+          if (col < g.N) {
+            const float a = acc[mt][0][i], b = acc[mt][1][i];
+            ((__attribute__((address_space(1))) bf16_t*)g.out)[p * g.ldo + col] =
+                f32_to_bf16(a / (1.f + expf(-a)) * b);
+          }
         } else {
-          static_cast<float*>(out)[(size_t)p * ldo + col] = acc[mt][0][i];
+#pragma unroll
+          for (int b = 0; b < 2; ++b) {
+            const int col = n0 + b * 64 + wn * 32 + fr;
+            if (col < g.N)
+              ((__attribute__((address_space(1))) float*)g.out)[blockIdx.z * g.split_stride + p * g.ldo + col] =
+                  acc[mt][b][i];
+          }
         }
       }
     }
   }
 }
 
-// Y[t, :] = sum_i gate[t,i] * Ybuf[inv[t*k+i], :], rounded once to bf16.  One block per token.
+template <bool SILU>
+__global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  if ((int)blockIdx.x >= *g.n_tiles) return;
+  const int e = g.tiles[3 * blockIdx.x];
+  const int row_lo = g.offsets[e] + g.tiles[3 * blockIdx.x + 1];
+  const int nrows = g.tiles[3 * blockIdx.x + 2];
+  if (nrows <= 64)
+    gemm_chunk<SILU, 1, 6>(g, smem, e, row_lo, nrows);
+  else if (nrows <= 128)
+    gemm_chunk<SILU, 2, 4>(g, smem, e, row_lo, nrows);
+  else
+    gemm_chunk<SILU, 4, 3>(g, smem, e, row_lo, nrows);
+}
+
+// Y[t, :] = sum_i gate[t,i] * (sum_z Ybuf[z][inv[t*k+i], :]), rounded once to bf16.  One block
+// per token; fixed summation order (z inner, i outer).
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ ybuf,
                                                        const int32_t* __restrict__ inv,
                                                        const float* __restrict__ gate,
-                                                       bf16_t* __restrict__ Y, int H, int k) {
+                                                       bf16_t* __restrict__ Y, int H, int k, int n_split,
+                                                       size_t split_stride) {
   const int t = blockIdx.x;
   for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) {
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int i = 0; i < k; ++i) {
       const int p = inv[t * k + i];
       if (p < 0) continue;
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      for (int z = 0; z < n_split; ++z) {
+        const f32x4 w = *reinterpret_cast<const f32x4*>(ybuf + z * split_stride + (size_t)p * H + c);
+        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+      }
       const float g = gate[t * k + i];
-      const f32x4 v = *reinterpret_cast<const f32x4*>(ybuf + (size_t)p * H + c);
       acc.x = fmaf(g, v.x, acc.x); acc.y = fmaf(g, v.y, acc.y);
       acc.z = fmaf(g, v.z, acc.z); acc.w = fmaf(g, v.w, acc.w);
     }
@@ -247,7 +320,7 @@ struct Carve {
 
 Carve carve(const Shape& sh, int32_t T, void* base) {
   const size_t n = (size_t)T * sh.k;
-  const size_t max_tiles = (size_t)sh.E + (n + BM - 1) / BM;
+  const size_t max_tiles = (size_t)sh.E + (n + BMX - 1) / BMX;
   char* p = static_cast<char*>(base);
   size_t off = 0;
   Carve c{};
@@ -255,22 +328,18 @@ Carve carve(const Shape& sh, int32_t T, void* base) {
   c.offsets = reinterpret_cast<int32_t*>(take((sh.E + 1) * sizeof(int32_t)));
   c.perm = reinterpret_cast<int32_t*>(take(n * sizeof(int32_t)));
   c.inv = reinterpret_cast<int32_t*>(take(n * sizeof(int32_t)));
-  c.tiles = reinterpret_cast<int32_t*>(take(2 * max_tiles * sizeof(int32_t)));
+  c.tiles = reinterpret_cast<int32_t*>(take(3 * max_tiles * sizeof(int32_t)));
   c.n_tiles = reinterpret_cast<int32_t*>(take(sizeof(int32_t)));
   c.hbuf = reinterpret_cast<bf16_t*>(take(n * sh.F * sizeof(bf16_t)));
-  c.ybuf = reinterpret_cast<float*>(take(n * sh.H * sizeof(float)));
+  c.ybuf = reinterpret_cast<float*>(take((size_t)MAX_KSPLIT * n * sh.H * sizeof(float)));
   c.total = off;
   return c;
 }
 
-constexpr size_t GEMM1_LDS = (2 * BM * BK + 2 * 2 * BN * BK) * sizeof(bf16_t);  // 64 KB
-constexpr size_t GEMM2_LDS = (2 * BM * BK + 2 * 1 * BN * BK) * sizeof(bf16_t);  // 48 KB
-bool g_prefill_attr_set = false;
-
 }  // namespace
 
 bool prefill_supported(const Shape& sh) {
-  return sh.dtype == ODMOE_BF16 && sh.H % BK == 0 && sh.F % BK == 0;
+  return sh.dtype == ODMOE_BF16 && sh.H % 64 == 0 && sh.F % 64 == 0;
 }
 
 size_t prefill_workspace_bytes(const Shape& sh, int32_t T) { return carve(sh, T, nullptr).total; }
@@ -282,36 +351,57 @@ hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* tab
   if (T <= 0) return hipSuccess;
   const Carve c = carve(sh, T, workspace);
   if (!workspace || c.total > workspace_bytes) return hipErrorInvalidValue;
-  if (!g_prefill_attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<true>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM1_LDS);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM2_LDS);
-    if (e != hipSuccess) return e;
-    g_prefill_attr_set = true;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
+    if (ea != hipSuccess) return ea;
+    ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<false>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
+    if (ea != hipSuccess) return ea;
+    attr_set = true;
   }
   const int n = T * sh.k;
-  const int max_tiles = sh.E + (n + BM - 1) / BM;
+  const int max_tiles = sh.E + (n + BMX - 1) / BMX;
   const size_t hf = (size_t)sh.H * sh.F;
 
   sort_slots_kernel<<<1, 1024, 0, s>>>(idx, n, sh.E, c.offsets, c.perm, c.inv, c.tiles, c.n_tiles);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
-  dim3 g1((sh.F + BN - 1) / BN, max_tiles);
-  grouped_gemm_kernel<true><<<g1, GEMM_THREADS, GEMM1_LDS, s>>>(
-      static_cast<const bf16_t*>(x), sh.H, c.perm, sh.k, table, table_off, 0, hf, c.offsets, c.tiles,
-      c.n_tiles, c.hbuf, sh.F, sh.F, sh.H);
+  GemmArgs g1{};
+  g1.A = static_cast<const bf16_t*>(x); g1.lda = sh.H; g1.a_slot = c.perm; g1.slot_div = sh.k;
+  g1.table = table; g1.table_off = table_off;
+  g1.b_off[0] = 0; g1.b_off[1] = hf; g1.b_row[0] = 0; g1.b_row[1] = 0;        // W1 and W3 rows n0..n0+63
+  g1.offsets = c.offsets; g1.tiles = c.tiles; g1.n_tiles = c.n_tiles;
+  g1.out = c.hbuf; g1.ldo = sh.F; g1.N = sh.F; g1.K = sh.H; g1.k_per_split = sh.H; g1.split_stride = 0;
+  dim3 grid1(max_tiles, (sh.F + BN / 2 - 1) / (BN / 2), 1);
+  grouped_gemm_kernel<true><<<grid1, GEMM_THREADS, GEMM_LDS, s>>>(g1);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
-  dim3 g2((sh.H + BN - 1) / BN, max_tiles);
-  grouped_gemm_kernel<false><<<g2, GEMM_THREADS, GEMM2_LDS, s>>>(
-      c.hbuf, sh.F, nullptr, 1, table, table_off, 2 * hf, 0, c.offsets, c.tiles, c.n_tiles, c.ybuf, sh.H,
-      sh.H, sh.F);
+  // w2 GEMM: few output tiles but a long K; split K so that the grid fills the chip.
+  const int nt2 = (sh.H + BN - 1) / BN;
+  const int ksteps = sh.F / BK;
+  int n_split = (4 * 256 + nt2 * 8 - 1) / (nt2 * 8);   // aim for >= 1024 blocks at ~8 chunks
+  if (n_split > MAX_KSPLIT) n_split = MAX_KSPLIT;
+  if (n_split > ksteps) n_split = ksteps;
+  if (n_split < 1) n_split = 1;
+  const int k_per_split = ((ksteps + n_split - 1) / n_split) * BK;
+  n_split = (sh.F + k_per_split - 1) / k_per_split;
+  const size_t split_stride = (size_t)n * sh.H;
+  GemmArgs g2{};
+  g2.A = c.hbuf; g2.lda = sh.F; g2.a_slot = nullptr; g2.slot_div = 1;
+  g2.table = table; g2.table_off = table_off;
+  g2.b_off[0] = 2 * hf; g2.b_off[1] = 2 * hf; g2.b_row[0] = 0; g2.b_row[1] = 64;  // W2 rows n0..n0+127
+  g2.offsets = c.offsets; g2.tiles = c.tiles; g2.n_tiles = c.n_tiles;
+  g2.out = c.ybuf; g2.ldo = sh.H; g2.N = sh.H; g2.K = sh.F; g2.k_per_split = k_per_split;
+  g2.split_stride = split_stride;
+  dim3 grid2(max_tiles, nt2, n_split);
+  grouped_gemm_kernel<false><<<grid2, GEMM_THREADS, GEMM_LDS, s>>>(g2);
   if ((e = hipGetLastError()) != hipSuccess) return e;
 
-  combine_kernel<<<T, 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k);
+  combine_kernel<<<T, 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split,
+                                   split_stride);
   return hipGetLastError();
 }
 
