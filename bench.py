@@ -45,6 +45,8 @@ def main() -> int:
                     help="tokens of the 32-layer cacheless stack to time (0 = skip)")
     ap.add_argument("--cpu-tokens", type=int, default=3, help="tokens the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--prefill-iters", type=int, default=5, help="timed prefill calls of 512 tokens (0 = skip)")
+    ap.add_argument("--probe-mib", type=int, default=672,
+                    help="size of the plain read/copy probe that measures the HBM and host-link ceilings (0 = skip)")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -68,6 +70,39 @@ def main() -> int:
     layer = synth.layer_weights(cfg, 0)
     X_np = synth.tokens(cfg, T)
     log(f"[bench] generated {cfg.name}: 8 experts x {cfg.expert_bytes / 1e6:.1f} MB in {time.time() - t0:.1f} s")
+
+    # ---- measured ceilings: a plain streaming read of HBM, a plain pinned host->HBM copy
+    ceilings = None
+    if args.probe_mib > 0:
+        nb = args.probe_mib << 20
+        src = torch.empty(4 * nb, dtype=torch.uint8, device="cuda:0").fill_(1)     # 4 windows, rotated
+        dst = torch.empty(nb, dtype=torch.uint8, device="cuda:0")
+        cur = torch.cuda.current_stream().cuda_stream
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        res = {}
+        for mode, name in ((1, "hbm_read_GBps"), (0, "hbm_copy_GBps")):
+            for w in range(2):
+                B.odmoe_probe_hbm(dst, src[w * nb:], nb, mode, cur)
+            torch.cuda.synchronize()
+            ev0.record()
+            for w in range(8):
+                B.odmoe_probe_hbm(dst, src[(w % 4) * nb:], nb, mode, cur)
+            ev1.record()
+            torch.cuda.synchronize()
+            res[name] = round(nb * 8 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9 * (2 if mode == 0 else 1), 1)
+        host = torch.empty(nb, dtype=torch.uint8, pin_memory=True)
+        dst.copy_(host, non_blocking=True)
+        torch.cuda.synchronize()
+        ev0.record()
+        for _ in range(4):
+            dst.copy_(host, non_blocking=True)
+        ev1.record()
+        torch.cuda.synchronize()
+        res["h2d_pinned_GBps"] = round(nb * 4 / (ev0.elapsed_time(ev1) * 1e-3) / 1e9, 2)
+        res["probe_MiB"] = args.probe_mib
+        ceilings = res
+        del src, dst, host
+        log(f"[bench] measured ceilings: {ceilings}")
 
     stack = harness.MoEStack(cfg, [layer])
     X = harness.to_device(X_np)
@@ -163,40 +198,55 @@ def main() -> int:
                    "tokens_per_expert": counts.tolist()}
         log(f"[bench] prefill: {prefill}")
 
-    # ---- cacheless 32-layer stack, short run (host-link roofline)
-    cacheless = None
-    if args.cacheless_tokens > 0:
-        c3 = synth.CONFIGS[3]
+    # ---- cacheless stacks, short runs (host-link roofline)
+    def run_cacheless(c, layers_u, n_tok, x_rows):
         t0 = time.time()
-        # one unique layer's experts in pinned memory, every layer aliases it: same bytes per token
-        st3 = harness.MoEStack(c3, [layer], unique_layers=1)
-        log(f"[bench] pinned arena ready in {time.time() - t0:.1f} s")
-        x3 = harness.to_device(X_np[0])
-        y3 = torch.empty_like(x3)
+        stc = harness.MoEStack(c, layers_u, unique_layers=len(layers_u))
+        log(f"[bench] {c.name}: pinned arena of {len(layers_u)} unique layer(s) ready in {time.time() - t0:.1f} s")
+        xs = [harness.to_device(r) for r in x_rows]
+        yc = torch.empty_like(xs[0])
         s = B.odmoe_stats()
-        B.odmoe_decode_step(st3.handle, x3, y3, None, None, s)         # warm-up token
+        B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)        # warm-up token
         torch.cuda.synchronize()
         t_start = time.perf_counter()
         loads = 0
-        for t in range(args.cacheless_tokens):
-            B.odmoe_decode_step(st3.handle, harness.to_device(X_np[t % T]), y3, None, None, s)
+        for t in range(n_tok):
+            B.odmoe_decode_step(stc.handle, xs[t % len(xs)], yc, None, None, s)
             loads += s.loads
         torch.cuda.synchronize()
         el = time.perf_counter() - t_start
+        idx_used = np.zeros((c.n_layers, c.top_k), np.int32)
+        B.odmoe_decode_step(stc.handle, xs[0], yc, None, idx_used, s)
+        t1 = time.perf_counter()
+        for t in range(n_tok):                                           # the same tokens with perfect hints
+            B.odmoe_decode_step(stc.handle, xs[0], yc, idx_used, None, s)
+        torch.cuda.synchronize()
+        el_hint = time.perf_counter() - t1
         s.t_step_ms = -1.0
-        B.odmoe_decode_step(st3.handle, x3, y3, None, None, s)         # one timed token for the breakdown
+        B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)        # one timed token for the breakdown
         load_ms = s.t_load_ms
         comp_ms = s.t_ffn_up_ms + s.t_ffn_down_ms + s.t_glue_ms
-        step_ms = el / args.cacheless_tokens * 1e3
-        h2d = loads * c3.expert_bytes / el / 1e9
-        cacheless = {"workload": c3.name, "tokens": args.cacheless_tokens, "unique_layers": 1,
-                     "tokens_per_s": round(args.cacheless_tokens / el, 4), "ms_per_token": round(step_ms, 2),
-                     "h2d_GBps": round(h2d, 2), "h2d_frac_of_pcie5_x16": round(h2d / PCIE5_X16_GBPS, 4),
-                     "copy_only_ms_per_token": round(load_ms, 2), "kernel_ms_per_token": round(comp_ms, 3),
-                     "step_over_max_compute_load": round(step_ms / max(load_ms, comp_ms), 4),
-                     "hbm_slot_bytes": B.odmoe_slot_pool_bytes(st3.handle)}
-        log(f"[bench] cacheless: {cacheless}")
-        st3.close()
+        step_ms = el / n_tok * 1e3
+        h2d = loads * c.expert_bytes / el / 1e9
+        out = {"workload": c.name, "tokens": n_tok, "unique_layers": len(layers_u),
+               "tokens_per_s": round(n_tok / el, 4), "ms_per_token": round(step_ms, 3),
+               "h2d_GBps": round(h2d, 2), "h2d_frac_of_pcie5_x16": round(h2d / PCIE5_X16_GBPS, 4),
+               "copy_only_ms_per_token": round(load_ms, 3), "kernel_ms_per_token": round(comp_ms, 3),
+               "step_over_max_compute_load": round(step_ms / max(load_ms, comp_ms), 4),
+               "ms_per_token_with_perfect_hints": round(el_hint / n_tok * 1e3, 3),
+               "hbm_slot_bytes": B.odmoe_slot_pool_bytes(stc.handle)}
+        stc.close()
+        log(f"[bench] cacheless: {out}")
+        return out
+
+    cacheless = None
+    cacheless_fine = None
+    if args.cacheless_tokens > 0:
+        cacheless = run_cacheless(synth.CONFIGS[3], [layer], args.cacheless_tokens, [X_np[t] for t in range(4)])
+        c5 = synth.CONFIGS[5]
+        layers5 = [synth.layer_weights(c5, l) for l in range(2)]
+        X5 = synth.tokens(c5, 4)
+        cacheless_fine = run_cacheless(c5, layers5, 8 * args.cacheless_tokens, [X5[t] for t in range(4)])
 
     # ---- CPU oracle on a bounded sample of the same workload
     cpu = None
@@ -229,7 +279,9 @@ def main() -> int:
                    "top_k": cfg.top_k, "n_layers": 1, "tokens_per_step": T, "batch": 1,
                    "weights": "resident in HBM"},
         "expert_gemv_hbm_GBps": None if gemv_gbps is None else round(gemv_gbps, 1),
-        "roofline": roofline, "cacheless": cacheless, "prefill": prefill, "cpu_baseline": cpu,
+        "measured_ceilings": ceilings,
+        "roofline": roofline, "cacheless": cacheless, "cacheless_fine_grained": cacheless_fine,
+        "prefill": prefill, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
     return 0

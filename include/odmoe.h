@@ -176,6 +176,15 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
 int odmoe_pinned_alloc(uint64_t bytes, void** out_host);
 int odmoe_pinned_free(void* host);
 
+/*
+ * Measurement aid (not part of the paper's method): a plain streaming kernel over `bytes`
+ * (multiple of 16) of device memory, enqueued on `stream`.  mode 0 copies src_dev to dst_dev
+ * (both `bytes` long); mode 1 only reads src_dev (dst_dev: at least 4 bytes of scratch).  It
+ * gives the measured HBM ceiling the expert GEMVs are compared with, and a kernel of known
+ * traffic to scale a profiler's byte counters by.
+ */
+int odmoe_probe_hbm(void* dst_dev, const void* src_dev, uint64_t bytes, int32_t mode, void* stream);
+
 /* Bytes of HBM the handle's slot pool occupies (S * expert bytes); 0 in resident mode. */
 uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h);
 

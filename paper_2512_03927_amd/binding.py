@@ -22,7 +22,7 @@ ODMOE_MAX_EXPERTS = 1024
 EXPORTS = (
     "odmoe_layer_init", "odmoe_layer_destroy", "odmoe_route_topk", "odmoe_expert_load_async",
     "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_decode_step", "odmoe_pinned_alloc",
-    "odmoe_pinned_free", "odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version",
+    "odmoe_pinned_free", "odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_probe_hbm",
 )
 
 
@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
     L.odmoe_decode_step.argtypes = [vp, vp, vp, vp, vp, C.POINTER(odmoe_stats)]
     L.odmoe_pinned_alloc.argtypes = [u64, C.POINTER(vp)]
     L.odmoe_pinned_free.argtypes = [vp]
+    L.odmoe_probe_hbm.argtypes = [vp, vp, u64, i32, vp]
     L.odmoe_slot_pool_bytes.argtypes = [vp]
     L.odmoe_slot_pool_bytes.restype = u64
     L.odmoe_last_error.restype = C.c_char_p
@@ -164,6 +165,10 @@ def odmoe_pinned_alloc(nbytes: int) -> int:
 
 def odmoe_pinned_free(host: Optional[int]) -> None:
     _check(lib().odmoe_pinned_free(host))
+
+
+def odmoe_probe_hbm(dst_dev, src_dev, nbytes: int, mode: int, stream: Optional[int] = None) -> None:
+    _check(lib().odmoe_probe_hbm(_ptr(dst_dev), _ptr(src_dev), nbytes, mode, stream))
 
 
 def odmoe_slot_pool_bytes(h: int) -> int:

@@ -688,6 +688,45 @@ hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
   return hipGetLastError();
 }
 
+// Plain streaming kernels over a buffer of known size: the measured HBM ceiling next to the
+// GEMVs, and the reference a profiler's byte counters are scaled by.  Each block walks one
+// contiguous span with 128-bit loads, eight in flight per lane.
+namespace {
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink) {
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t b0 = (size_t)blockIdx.x * per, b1 = b0 + per < n16 ? b0 + per : n16;
+  uint32_t acc = 0;
+  size_t i = b0 + threadIdx.x;
+  for (; i + 7 * 256 < b1; i += 8 * 256) {
+    u32x4 q[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) q[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= q[u].x ^ q[u].y ^ q[u].z ^ q[u].w;
+  }
+  for (; i < b1; i += 256) { const u32x4 q = src[i]; acc ^= q.x ^ q.y ^ q.z ^ q.w; }
+  if (acc == 0x9e3779b9u) sink[0] = acc;  // practically never: keeps the loads alive
+}
+__global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict__ src,
+                                                          u32x4* __restrict__ dst, size_t n16) {
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t b0 = (size_t)blockIdx.x * per, b1 = b0 + per < n16 ? b0 + per : n16;
+  for (size_t i = b0 + threadIdx.x; i < b1; i += 256) dst[i] = src[i];
+}
+}  // namespace
+
+hipError_t launch_probe(hipStream_t s, void* dst, const void* src, size_t bytes, int mode) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  const int grid = num_cu() * 8;
+  if (mode == 1)
+    probe_read_kernel<<<grid, 256, 0, s>>>(static_cast<const u32x4*>(src), n16, static_cast<uint32_t*>(dst));
+  else
+    probe_copy_kernel<<<grid, 256, 0, s>>>(static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), n16);
+  return hipGetLastError();
+}
+
 hipError_t launch_glue(hipStream_t s, const Shape& sh, const void* x, const void* y, void* x_next) {
   if (sh.dtype == ODMOE_F32)
     glue_kernel<float><<<1, 1024, 0, s>>>(static_cast<const float*>(x), static_cast<const float*>(y),

@@ -47,6 +47,10 @@ hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* tab
                           int32_t table_off, const int32_t* idx, const float* gate, const void* x,
                           int32_t T, void* y, void* workspace, size_t workspace_bytes);
 
+// Plain streaming kernel over `bytes` (multiple of 16): mode 0 copies src to dst, mode 1 only
+// reads src (dst: 4 bytes of scratch).
+hipError_t launch_probe(hipStream_t s, void* dst, const void* src, size_t bytes, int mode);
+
 // One-time per-process kernel attribute setup (large dynamic LDS).
 hipError_t kernels_init();
 

@@ -186,6 +186,14 @@ int odmoe_pinned_free(void* host) {
   return ODMOE_OK;
 }
 
+int odmoe_probe_hbm(void* dst_dev, const void* src_dev, uint64_t bytes, int32_t mode, void* stream) {
+  if (!dst_dev || !src_dev) return fail(ODMOE_EINVAL, "dst/src is NULL");
+  if (bytes % 16) return fail(ODMOE_EINVAL, "bytes must be a multiple of 16");
+  if (mode != 0 && mode != 1) return fail(ODMOE_EINVAL, "mode must be 0 (copy) or 1 (read)");
+  HIP_TRY(launch_probe(static_cast<hipStream_t>(stream), dst_dev, src_dev, bytes, mode));
+  return ODMOE_OK;
+}
+
 uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h) {
   return h && h->pool ? (uint64_t)h->cfg.n_slots * h->expert_bytes : 0;
 }
