@@ -11,7 +11,8 @@ activations already in HBM when the timed region starts.
 
 Also reported on the same JSON line:
   roofline      the dominant kernel (w1/w3 GEMV + SiLU) against the HBM peak, timed with
-                HIP events on the compute stream in a second pass over the same steps
+                HIP events on the compute stream in a second pass over the same tokens
+                (the kernel launched back to back for all 256 tokens between two events)
   cacheless     a short run of the 32-layer cacheless stack (experts in pinned host memory,
                 4 HBM slots): H2D expert-load GB/s, tokens/s, step / max(compute, load)
   cpu_baseline  the float64 NumPy oracle on a bounded sample of the same tokens
@@ -131,18 +132,9 @@ def main() -> int:
     roofline = None
     gemv_gbps = None
     if not args.no_kernel_pass:
-        st = B.odmoe_stats()
-        t_up = t_down = t_route = 0.0
-        n = 0
-        for _ in range(max(1, min(args.steps, 3))):
-            for t in range(T):
-                st.t_step_ms = -1.0
-                B.odmoe_decode_step(h, X[t], Y[t], None, None, st)
-                t_up += st.t_ffn_up_ms
-                t_down += st.t_ffn_down_ms
-                t_route += st.t_route_ms
-                n += 1
-        up_ms, down_ms, route_ms = t_up / n, t_down / n, t_route / n
+        # each kernel launched back to back for the same 256 tokens, HIP events around each pass
+        route_us, up_us, down_us = B.odmoe_time_decode_kernels(h, 0, X, T, max(1, min(args.steps, 4)))
+        up_ms, down_ms, route_ms = up_us * 1e-3, down_us * 1e-3, route_us * 1e-3
         achieved = up_bytes / (up_ms * 1e-3) / 1e9
         gemv_gbps = (up_bytes + down_bytes) / ((up_ms + down_ms) * 1e-3) / 1e9
         traffic = None

@@ -185,6 +185,16 @@ int odmoe_pinned_free(void* host);
  */
 int odmoe_probe_hbm(void* dst_dev, const void* src_dev, uint64_t bytes, int32_t mode, void* stream);
 
+/*
+ * Measurement aid: average duration, in microseconds, of each decode kernel of layer `layer`
+ * (resident mode) over the n_tokens rows of x_dev[T,H], taken with HIP events on the compute
+ * stream around `reps` passes in which the same kernel is launched back to back for every token
+ * (token t uses the experts the router picks for it, as in odmoe_decode_step).  Blocks.
+ * Allocates and frees small temporaries.
+ */
+int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t n_tokens,
+                              int32_t reps, float* route_us, float* ffn_up_us, float* ffn_down_us);
+
 /* Bytes of HBM the handle's slot pool occupies (S * expert bytes); 0 in resident mode. */
 uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h);
 

@@ -23,6 +23,7 @@ EXPORTS = (
     "odmoe_layer_init", "odmoe_layer_destroy", "odmoe_route_topk", "odmoe_expert_load_async",
     "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_decode_step", "odmoe_pinned_alloc",
     "odmoe_pinned_free", "odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_probe_hbm",
+    "odmoe_time_decode_kernels",
 )
 
 
@@ -71,6 +72,8 @@ def lib() -> C.CDLL:
     L.odmoe_pinned_alloc.argtypes = [u64, C.POINTER(vp)]
     L.odmoe_pinned_free.argtypes = [vp]
     L.odmoe_probe_hbm.argtypes = [vp, vp, u64, i32, vp]
+    L.odmoe_time_decode_kernels.argtypes = [vp, i32, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float),
+                                            C.POINTER(C.c_float)]
     L.odmoe_slot_pool_bytes.argtypes = [vp]
     L.odmoe_slot_pool_bytes.restype = u64
     L.odmoe_last_error.restype = C.c_char_p
@@ -169,6 +172,14 @@ def odmoe_pinned_free(host: Optional[int]) -> None:
 
 def odmoe_probe_hbm(dst_dev, src_dev, nbytes: int, mode: int, stream: Optional[int] = None) -> None:
     _check(lib().odmoe_probe_hbm(_ptr(dst_dev), _ptr(src_dev), nbytes, mode, stream))
+
+
+def odmoe_time_decode_kernels(h: int, layer: int, x_dev, n_tokens: int, reps: int = 1):
+    """(route_us, ffn_up_us, ffn_down_us): average kernel durations from HIP events."""
+    r, u, d = C.c_float(), C.c_float(), C.c_float()
+    _check(lib().odmoe_time_decode_kernels(h, layer, _ptr(x_dev), n_tokens, reps, C.byref(r), C.byref(u),
+                                           C.byref(d)))
+    return r.value, u.value, d.value
 
 
 def odmoe_slot_pool_bytes(h: int) -> int:

@@ -73,6 +73,7 @@ __device__ __forceinline__ double wave_sum(double v) {
 }
 
 __device__ __forceinline__ const void* expert_ptr(const ExpertSrc& s, const int32_t* idx, int i) {
+  if (s.resolved) return s.resolved[i];
   return s.table ? s.table[s.table_off + idx[i]] : s.slot[i];
 }
 
@@ -167,66 +168,76 @@ __device__ __forceinline__ void stage_vec(const T* __restrict__ src, float* __re
 // reference rounded the same way regardless of summation order.  Ties: lowest index first.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void route_topk_kernel(const T* __restrict__ Wg,
+__global__ __launch_bounds__(512) void route_topk_kernel(const T* __restrict__ Wg,
                                                           const float* __restrict__ bias,
                                                           const T* __restrict__ x, int H, int E, int k,
                                                           int32_t* __restrict__ idx,
                                                           float* __restrict__ gate,
-                                                          int32_t* __restrict__ idx_mirror) {
+                                                          int32_t* __restrict__ idx_mirror,
+                                                          const void* const* __restrict__ table,
+                                                          int table_off,
+                                                          const void** __restrict__ eptr_out) {
   constexpr int VEC = DT<T>::VEC;
   __shared__ float slog[ODMOE_MAX_EXPERTS];
+  __shared__ float sel_v[ODMOE_MAX_TOPK];
+  __shared__ int sel_i[ODMOE_MAX_TOPK];
   const int t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const T* xt = x + (size_t)t * H;
   const int nvec = H / VEC;
+  // NaN logits take no position in the order below; pre-filling the selection keeps every
+  // index in range even then (which experts are picked is unspecified in that case).
+  if (threadIdx.x < k) { sel_v[threadIdx.x] = 0.f; sel_i[threadIdx.x] = threadIdx.x; }
   for (int e = wave; e < E; e += nw) {
     const T* row = Wg + (size_t)e * H;
-    double acc = 0.0;
-    for (int v = lane; v < nvec; v += WAVE) {
+    double acc0 = 0.0, acc1 = 0.0;  // two chains: half the dependent-FMA latency
+    int v = lane;
+    for (; v + WAVE < nvec; v += 2 * WAVE) {
+      float fw[VEC], fx[VEC], gw[VEC], gx[VEC];
+      DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
+      DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
+      DT<T>::unpack(load16(row + (size_t)(v + WAVE) * VEC), gw);
+      DT<T>::unpack(load16(xt + (size_t)(v + WAVE) * VEC), gx);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        acc0 = fma((double)fw[j], (double)fx[j], acc0);
+        acc1 = fma((double)gw[j], (double)gx[j], acc1);
+      }
+    }
+    for (; v < nvec; v += WAVE) {
       float fw[VEC], fx[VEC];
       DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
       DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
 #pragma unroll
-      for (int j = 0; j < VEC; ++j) acc = fma((double)fw[j], (double)fx[j], acc);
+      for (int j = 0; j < VEC; ++j) acc0 = fma((double)fw[j], (double)fx[j], acc0);
     }
-    acc = wave_sum(acc);
+    const double acc = wave_sum(acc0 + acc1);
     if (lane == 0) slog[e] = (float)(acc + (bias ? (double)bias[e] : 0.0));
   }
   __syncthreads();
-  if (wave != 0) return;
 
-  // k rounds of "best element strictly after the previous pick" in the total order
-  // (logit descending, index ascending).
-  const int NONE = 0x7fffffff;
-  float prev_v = 0.f, my_v = 0.f;
-  int prev_i = -1, my_i = 0;
-  for (int i = 0; i < k; ++i) {
-    float bv = 0.f;
-    int bi = NONE;
-    for (int e = lane; e < E; e += WAVE) {
-      float v = slog[e];
-      bool after = (i == 0) || (v < prev_v) || (v == prev_v && e > prev_i);
-      bool better = (bi == NONE) || (v > bv) || (v == bv && e < bi);
-      if (after && better) { bv = v; bi = e; }
+  // Position of every expert in the total order (logit descending, index ascending): the
+  // number of experts that come before it.  Experts at positions < k are the selection.
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    const float v = slog[e];
+    int before = 0;
+    for (int j = 0; j < E; ++j) {
+      const float u = slog[j];
+      before += (u > v) || (u == v && j < e);
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      float ov = __shfl_xor(bv, off, WAVE);
-      int oi = __shfl_xor(bi, off, WAVE);
-      bool take = (oi != NONE) && ((bi == NONE) || (ov > bv) || (ov == bv && oi < bi));
-      if (take) { bv = ov; bi = oi; }
-    }
-    prev_v = bv; prev_i = bi;
-    if (lane == i) { my_v = bv; my_i = bi; }
+    if (before < k) { sel_v[before] = v; sel_i[before] = e; }
   }
-  const float v0 = __shfl(my_v, 0, WAVE);
-  const float u = (lane < k) ? expf(my_v - v0) : 0.f;
-  float s = 0.f;
-  for (int i = 0; i < k; ++i) s += __shfl(u, i, WAVE);  // fixed order i = 0..k-1
-  if (lane < k) {
-    idx[(size_t)t * k + lane] = my_i;
-    gate[(size_t)t * k + lane] = u / s;
-    if (idx_mirror) idx_mirror[(size_t)t * k + lane] = my_i;
+  __syncthreads();
+  if (threadIdx.x < k) {
+    const int i = threadIdx.x;
+    const float v0 = sel_v[0];
+    float s = 0.f;
+    for (int j = 0; j < k; ++j) s += expf(sel_v[j] - v0);  // fixed order j = 0..k-1
+    const int e = sel_i[i];
+    idx[(size_t)t * k + i] = e;
+    gate[(size_t)t * k + i] = expf(sel_v[i] - v0) / s;
+    if (idx_mirror) idx_mirror[(size_t)t * k + i] = e;
+    if (eptr_out) eptr_out[(size_t)t * k + i] = table[table_off + e];
   }
 }
 
@@ -522,16 +533,20 @@ hipError_t kernels_init() {
 
 hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
                              const void* x, int32_t T, int32_t* idx, float* gate,
-                             int32_t* idx_mirror) {
+                             int32_t* idx_mirror, const void* const* table, int32_t table_off,
+                             const void** eptr_out) {
   if (T <= 0) return hipSuccess;
+  // one wave per expert up to 8 waves; NaN logits never enter the selection (k entries may then
+  // stay unwritten: documented as unspecified)
+  const int threads = sh.E >= 8 ? 512 : (sh.E >= 4 ? 256 : 128);
   if (sh.dtype == ODMOE_F32)
-    route_topk_kernel<float><<<T, 256, 0, s>>>(static_cast<const float*>(Wg), b,
-                                               static_cast<const float*>(x), sh.H, sh.E, sh.k, idx,
-                                               gate, idx_mirror);
+    route_topk_kernel<float><<<T, threads, 0, s>>>(static_cast<const float*>(Wg), b,
+                                                   static_cast<const float*>(x), sh.H, sh.E, sh.k, idx,
+                                                   gate, idx_mirror, table, table_off, eptr_out);
   else
-    route_topk_kernel<bf16_t><<<T, 256, 0, s>>>(static_cast<const bf16_t*>(Wg), b,
-                                                static_cast<const bf16_t*>(x), sh.H, sh.E, sh.k,
-                                                idx, gate, idx_mirror);
+    route_topk_kernel<bf16_t><<<T, threads, 0, s>>>(static_cast<const bf16_t*>(Wg), b,
+                                                    static_cast<const bf16_t*>(x), sh.H, sh.E, sh.k,
+                                                    idx, gate, idx_mirror, table, table_off, eptr_out);
   return hipGetLastError();
 }
 

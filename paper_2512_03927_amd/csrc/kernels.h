@@ -9,11 +9,13 @@
 namespace odmoe {
 
 // Where the weights of the i-th selected expert (rank i in idx) live.
-//   resident : table != nullptr, pointer = table[table_off + idx[t*k + i]]   (device table, L*E entries)
-//   cacheless: table == nullptr, pointer = slot[i]                           (HBM slot bases by rank)
+//   resolved : resolved != nullptr, pointer = resolved[i]   (device array the router kernel filled)
+//   resident : table != nullptr, pointer = table[table_off + idx[i]]   (device table, L*E entries)
+//   cacheless: otherwise, pointer = slot[i]                            (HBM slot bases by rank)
 struct ExpertSrc {
   const void* slot[ODMOE_MAX_TOPK];
   const void* const* table;
+  const void* const* resolved;
   int32_t table_off;
 };
 
@@ -23,10 +25,13 @@ struct Shape {
 };
 
 // Router GEMV + top-k + gate for T tokens.  idx_mirror (may be null) is a second int32[T*k]
-// destination (host-mapped pinned memory) written together with idx.
+// destination (host-mapped pinned memory) written together with idx.  With eptr_out != null the
+// kernel also stores table[table_off + idx] there (T*k pointers), which saves the FFN kernels
+// one dependent load.
 hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
                              const void* x, int32_t T, int32_t* idx, float* gate,
-                             int32_t* idx_mirror);
+                             int32_t* idx_mirror, const void* const* table, int32_t table_off,
+                             const void** eptr_out);
 
 // h[i, :] = silu(W1 x) * (W3 x) for the k selected experts of ONE token.  hbuf: fp32 [k, F].
 hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,

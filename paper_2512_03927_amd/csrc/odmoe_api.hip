@@ -68,6 +68,7 @@ struct odmoe_layer {
   float* gate_dev = nullptr;    // [L*k]
   int32_t* idx_pin = nullptr;   // pinned host [L*k], written by the router kernel
   int32_t* idx_pin_dev = nullptr;
+  const void** eptr_dev = nullptr;  // resident: [L*k] expert pointers resolved by the router kernel
   hipEvent_t route_ev = nullptr;
   void* prefill_ws = nullptr;
   size_t prefill_ws_bytes = 0;
@@ -115,6 +116,7 @@ void free_all(odmoe_layer* h) {
   if (h->ybuf) (void)hipFree(h->ybuf);
   if (h->idx_dev) (void)hipFree(h->idx_dev);
   if (h->gate_dev) (void)hipFree(h->gate_dev);
+  if (h->eptr_dev) (void)hipFree((void*)h->eptr_dev);
   if (h->idx_pin) (void)hipHostFree(h->idx_pin);
   if (h->prefill_ws) (void)hipFree(h->prefill_ws);
   if (h->own_copy && h->copy) (void)hipStreamDestroy(h->copy);
@@ -194,6 +196,72 @@ int odmoe_probe_hbm(void* dst_dev, const void* src_dev, uint64_t bytes, int32_t 
   return ODMOE_OK;
 }
 
+int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t n_tokens,
+                              int32_t reps, float* route_us, float* ffn_up_us, float* ffn_down_us) {
+  int rc = check_layer(h, layer);
+  if (rc) return rc;
+  if (h->pool) return fail(ODMOE_EINVAL, "resident mode only");
+  if (!x_dev || n_tokens < 1 || reps < 1 || !route_us || !ffn_up_us || !ffn_down_us)
+    return fail(ODMOE_EINVAL, "bad arguments");
+  const int k = h->cfg.top_k;
+  const size_t row = (size_t)h->cfg.hidden * h->esize;
+  int32_t* idx = nullptr;
+  float* gate = nullptr;
+  void* y = nullptr;
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  auto cleanup = [&]() {
+    if (idx) (void)hipFree(idx);
+    if (gate) (void)hipFree(gate);
+    if (y) (void)hipFree(y);
+    for (auto e : ev) if (e) (void)hipEventDestroy(e);
+  };
+#define T_TRY(expr)                                                                              \
+  do {                                                                                           \
+    hipError_t e__ = (expr);                                                                     \
+    if (e__ != hipSuccess) {                                                                     \
+      cleanup();                                                                                 \
+      return fail(ODMOE_EHIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+    }                                                                                            \
+  } while (0)
+  T_TRY(hipMalloc(&idx, (size_t)n_tokens * k * sizeof(int32_t)));
+  T_TRY(hipMalloc(&gate, (size_t)n_tokens * k * sizeof(float)));
+  T_TRY(hipMalloc(&y, row));
+  for (auto& e : ev) T_TRY(hipEventCreate(&e));
+  ExpertSrc src{};
+  src.table = h->table_dev;
+  src.table_off = layer * h->cfg.n_experts;
+  const float* bias = static_cast<const float*>(h->router_b[layer]);
+  // warm-up + the routing every later launch uses
+  T_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer], bias, x_dev, n_tokens, idx, gate, nullptr,
+                          nullptr, 0, nullptr));
+  T_TRY(hipEventRecord(ev[0], h->compute));
+  for (int r = 0; r < reps; ++r)
+    for (int t = 0; t < n_tokens; ++t)
+      T_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer], bias,
+                              static_cast<const char*>(x_dev) + t * row, 1, idx + (size_t)t * k,
+                              gate + (size_t)t * k, nullptr, nullptr, 0, nullptr));
+  T_TRY(hipEventRecord(ev[1], h->compute));
+  for (int r = 0; r < reps; ++r)
+    for (int t = 0; t < n_tokens; ++t)
+      T_TRY(launch_ffn_up(h->compute, h->sh, src, idx + (size_t)t * k,
+                          static_cast<const char*>(x_dev) + t * row, h->hbuf));
+  T_TRY(hipEventRecord(ev[2], h->compute));
+  for (int r = 0; r < reps; ++r)
+    for (int t = 0; t < n_tokens; ++t)
+      T_TRY(launch_ffn_down(h->compute, h->sh, src, idx + (size_t)t * k, gate + (size_t)t * k, h->hbuf, y));
+  T_TRY(hipEventRecord(ev[3], h->compute));
+  T_TRY(hipEventSynchronize(ev[3]));
+  float ms[3];
+  for (int i = 0; i < 3; ++i) T_TRY(hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]));
+#undef T_TRY
+  const float n = (float)reps * (float)n_tokens;
+  *route_us = ms[0] * 1e3f / n;
+  *ffn_up_us = ms[1] * 1e3f / n;
+  *ffn_down_us = ms[2] * 1e3f / n;
+  cleanup();
+  return ODMOE_OK;
+}
+
 uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h) {
   return h && h->pool ? (uint64_t)h->cfg.n_slots * h->expert_bytes : 0;
 }
@@ -248,6 +316,7 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
   INIT_TRY(hipEventCreateWithFlags(&h->route_ev, hipEventDisableTiming), ODMOE_EHIP);
 
   if (S == 0) {
+    INIT_TRY(hipMalloc((void**)&h->eptr_dev, (size_t)L * k * sizeof(void*)), ODMOE_ENOMEM);
     INIT_TRY(hipMalloc((void**)&h->table_dev, (size_t)L * E * sizeof(void*)), ODMOE_ENOMEM);
     INIT_TRY(hipMemcpy((void*)h->table_dev, h->expert_w.data(), (size_t)L * E * sizeof(void*),
                        hipMemcpyHostToDevice),
@@ -294,7 +363,7 @@ int odmoe_route_topk(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t
   if (!x_dev || !idx_dev || !gate_dev) return fail(ODMOE_EINVAL, "x/idx/gate is NULL");
   HIP_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer],
                             static_cast<const float*>(h->router_b[layer]), x_dev, n_tokens, idx_dev,
-                            gate_dev, nullptr));
+                            gate_dev, nullptr, nullptr, 0, nullptr));
   return ODMOE_OK;
 }
 
@@ -446,7 +515,8 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
     }
     if (timed) HIP_TRY(hipEventRecord(TE(l, 0), h->compute));
     HIP_TRY(launch_route_topk(h->compute, h->sh, h->router_w[l], static_cast<const float*>(h->router_b[l]),
-                              cur, 1, idx_l, gate_l, h->idx_pin_dev + (size_t)l * k));
+                              cur, 1, idx_l, gate_l, h->idx_pin_dev + (size_t)l * k, h->table_dev, l * E,
+                              h->sched ? nullptr : h->eptr_dev + (size_t)l * k));
 
     ExpertSrc src{};
     int32_t slots[ODMOE_MAX_TOPK];
@@ -466,6 +536,7 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
     } else {
       src.table = h->table_dev;
       src.table_off = l * E;
+      src.resolved = h->eptr_dev + (size_t)l * k;
     }
 
     void* y_l = (h->cfg.glue == 0) ? (last ? y_dev : h->xbuf[l & 1]) : h->ybuf;
