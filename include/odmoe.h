@@ -143,8 +143,13 @@ int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert);
  *              matrix cores take bf16 operands).  Other shapes fall back to the per-token path.
  *   evict_after  cacheless mode: nonzero releases the experts' slots after the kernels that
  *              read them (the paper's prompt eviction).  Ignored in resident mode.
- * Cacheless mode supports n_tokens == 1 here.  The compute stream waits (stream side) for
- * each needed expert's copy.  ESTATE if a needed expert is neither loading nor ready.
+ * Cacheless mode: n_tokens == 1 needs every chosen expert loading or ready (ESTATE otherwise);
+ * the compute stream waits (stream side) for each copy.  n_tokens >= 16 (bf16, hidden and ffn
+ * multiples of 64) is the prefill of Section 3.3 from host memory: the call itself streams
+ * every expert that received tokens into a slot exactly once (experts already loading or
+ * ready are used as they are), runs that expert's grouped GEMMs when its copy has landed, and
+ * with evict_after releases the slot for the next expert, so that copies overlap GEMMs.
+ * 1 < n_tokens < 16 is EINVAL in cacheless mode.
  */
 int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev,
                      const float* gate_dev, const int32_t* idx_host, const void* x_dev,
@@ -194,6 +199,18 @@ int odmoe_probe_hbm(void* dst_dev, const void* src_dev, uint64_t bytes, int32_t 
  */
 int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t n_tokens,
                               int32_t reps, float* route_us, float* ffn_up_us, float* ffn_down_us);
+
+/*
+ * Longest expert-loading time that causes no compute stall (Section 3.1, load-window
+ * equation, with its G read as the number of groups so that it reproduces the worked example
+ * 4 t^M + 3 t^W of the four-group testbed):  n_groups * t_main + (n_groups - 1) * t_worker.
+ * Host-only arithmetic; n_groups < 1 gives 0.
+ */
+double odmoe_load_window_ms(int32_t n_groups, double t_main_ms, double t_worker_ms);
+
+/* Number of slot groups of the handle, floor(n_slots / top_k): the one-GPU counterpart of the
+ * paper's N_W / G worker groups (Section 3.1); 0 in resident mode. */
+int32_t odmoe_slot_groups(const odmoe_layer_t* h);
 
 /* Bytes of HBM the handle's slot pool occupies (S * expert bytes); 0 in resident mode. */
 uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h);

@@ -23,7 +23,7 @@ EXPORTS = (
     "odmoe_layer_init", "odmoe_layer_destroy", "odmoe_route_topk", "odmoe_expert_load_async",
     "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_decode_step", "odmoe_pinned_alloc",
     "odmoe_pinned_free", "odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_probe_hbm",
-    "odmoe_time_decode_kernels",
+    "odmoe_time_decode_kernels", "odmoe_load_window_ms", "odmoe_slot_groups",
 )
 
 
@@ -74,12 +74,17 @@ def lib() -> C.CDLL:
     L.odmoe_probe_hbm.argtypes = [vp, vp, u64, i32, vp]
     L.odmoe_time_decode_kernels.argtypes = [vp, i32, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float),
                                             C.POINTER(C.c_float)]
+    L.odmoe_load_window_ms.argtypes = [i32, C.c_double, C.c_double]
+    L.odmoe_load_window_ms.restype = C.c_double
+    L.odmoe_slot_groups.argtypes = [vp]
+    L.odmoe_slot_groups.restype = i32
     L.odmoe_slot_pool_bytes.argtypes = [vp]
     L.odmoe_slot_pool_bytes.restype = u64
     L.odmoe_last_error.restype = C.c_char_p
     L.odmoe_version.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version"):
+        if name not in ("odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_load_window_ms",
+                        "odmoe_slot_groups"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -180,6 +185,14 @@ def odmoe_time_decode_kernels(h: int, layer: int, x_dev, n_tokens: int, reps: in
     _check(lib().odmoe_time_decode_kernels(h, layer, _ptr(x_dev), n_tokens, reps, C.byref(r), C.byref(u),
                                            C.byref(d)))
     return r.value, u.value, d.value
+
+
+def odmoe_load_window_ms(n_groups: int, t_main_ms: float, t_worker_ms: float) -> float:
+    return float(lib().odmoe_load_window_ms(n_groups, t_main_ms, t_worker_ms))
+
+
+def odmoe_slot_groups(h: int) -> int:
+    return int(lib().odmoe_slot_groups(h))
 
 
 def odmoe_slot_pool_bytes(h: int) -> int:

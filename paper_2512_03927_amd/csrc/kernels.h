@@ -51,6 +51,18 @@ size_t prefill_workspace_bytes(const Shape& sh, int32_t T);
 hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* table,
                           int32_t table_off, const int32_t* idx, const float* gate, const void* x,
                           int32_t T, void* y, void* workspace, size_t workspace_bytes);
+// The same in phases, for experts that are streamed in one at a time: bucket the token-slots;
+// run both GEMMs for the chunk-list entries [tile_first, tile_first + tile_count) with the weights
+// at expert_override (or from the table when null); combine.  Chunk-list entries are ordered by
+// expert; prefill_chunks_of(count) is the number of entries of an expert with `count` token-slots.
+hipError_t prefill_sort(hipStream_t s, const Shape& sh, const int32_t* idx, int32_t T, void* workspace,
+                        size_t workspace_bytes);
+hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* table, int32_t table_off,
+                         const void* expert_override, int32_t tile_first, int32_t tile_count,
+                         const void* x, int32_t T, void* workspace);
+hipError_t prefill_combine(hipStream_t s, const Shape& sh, const float* gate, int32_t T, void* y,
+                           void* workspace);
+int prefill_chunks_of(int32_t count);
 
 // Plain streaming kernel over `bytes` (multiple of 16): mode 0 copies src to dst, mode 1 only
 // reads src (dst: 4 bytes of scratch).

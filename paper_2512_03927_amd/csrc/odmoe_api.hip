@@ -156,6 +156,20 @@ int mark_used(odmoe_layer* h, int32_t slot) {
   return ODMOE_OK;
 }
 
+int ensure_prefill_ws(odmoe_layer* h, int32_t n_tokens) {
+  const size_t need = prefill_workspace_bytes(h->sh, n_tokens);
+  if (need > h->prefill_ws_bytes) {
+    if (h->prefill_ws) HIP_TRY(hipFree(h->prefill_ws));  // hipFree waits for the device
+    h->prefill_ws = nullptr;
+    h->prefill_ws_bytes = 0;
+    hipError_t e = hipMalloc(&h->prefill_ws, need);
+    if (e != hipSuccess)
+      return fail(ODMOE_ENOMEM, "prefill workspace of %zu bytes: %s", need, hipGetErrorString(e));
+    h->prefill_ws_bytes = need;
+  }
+  return ODMOE_OK;
+}
+
 int run_ffn_one_token(odmoe_layer* h, const ExpertSrc& src, const int32_t* idx_dev,
                       const float* gate_dev, const void* x, void* y, hipEvent_t between = nullptr) {
   HIP_TRY(launch_ffn_up(h->compute, h->sh, src, idx_dev, x, h->hbuf));
@@ -260,6 +274,15 @@ int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev
   *ffn_down_us = ms[2] * 1e3f / n;
   cleanup();
   return ODMOE_OK;
+}
+
+double odmoe_load_window_ms(int32_t n_groups, double t_main_ms, double t_worker_ms) {
+  if (n_groups < 1) return 0.0;
+  return n_groups * t_main_ms + (n_groups - 1) * t_worker_ms;
+}
+
+int32_t odmoe_slot_groups(const odmoe_layer_t* h) {
+  return h && h->pool ? h->cfg.n_slots / h->cfg.top_k : 0;
 }
 
 uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h) {
@@ -413,15 +436,7 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
     src.table = h->table_dev;
     src.table_off = layer * E;
     if (n_tokens >= 16 && prefill_supported(h->sh)) {
-      const size_t need = prefill_workspace_bytes(h->sh, n_tokens);
-      if (need > h->prefill_ws_bytes) {
-        if (h->prefill_ws) HIP_TRY(hipFree(h->prefill_ws));  // hipFree waits for the device
-        h->prefill_ws = nullptr;
-        h->prefill_ws_bytes = 0;
-        hipError_t e = hipMalloc(&h->prefill_ws, need);
-        if (e != hipSuccess) return fail(ODMOE_ENOMEM, "prefill workspace of %zu bytes: %s", need, hipGetErrorString(e));
-        h->prefill_ws_bytes = need;
-      }
+      if ((rc = ensure_prefill_ws(h, n_tokens))) return rc;
       HIP_TRY(launch_prefill(h->compute, h->sh, h->table_dev, layer * E, idx_dev, gate_dev, x_dev,
                              n_tokens, y_dev, h->prefill_ws, h->prefill_ws_bytes));
       return ODMOE_OK;
@@ -434,8 +449,52 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
     return ODMOE_OK;
   }
 
-  // cacheless
-  if (n_tokens != 1) return fail(ODMOE_EINVAL, "cacheless mode computes one token per call");
+  // cacheless prefill (paper Section 3.3 on one GPU): every expert that received tokens is
+  // streamed from host memory into a slot exactly once, its grouped GEMMs run as soon as its
+  // copy has landed, and the slot is handed to the next expert: with S >= 2 slots the copy of
+  // the next expert overlaps the GEMMs of the current one.
+  if (n_tokens >= 16) {
+    if (!prefill_supported(h->sh))
+      return fail(ODMOE_EINVAL, "cacheless batches need bf16 and hidden/ffn multiples of 64");
+    if ((rc = ensure_prefill_ws(h, n_tokens))) return rc;
+    const size_t n = (size_t)n_tokens * k;
+    std::vector<int32_t> ids_all(n);
+    if (idx_host) {
+      memcpy(ids_all.data(), idx_host, n * sizeof(int32_t));
+    } else {
+      HIP_TRY(hipMemcpyAsync(ids_all.data(), idx_dev, n * sizeof(int32_t), hipMemcpyDeviceToHost, h->compute));
+      HIP_TRY(hipStreamSynchronize(h->compute));
+    }
+    std::vector<int32_t> count(E, 0);
+    for (size_t i = 0; i < n; ++i)
+      if (ids_all[i] >= 0 && ids_all[i] < E) ++count[ids_all[i]];
+    HIP_TRY(prefill_sort(h->compute, h->sh, idx_dev, n_tokens, h->prefill_ws, h->prefill_ws_bytes));
+    int tile_first = 0;
+    for (int e = 0; e < E; ++e) {
+      const int tiles_e = prefill_chunks_of(count[e]);
+      if (tiles_e == 0) continue;
+      int s = h->pool->find(layer, e);
+      if (s < 0) {
+        s = h->pool->acquire(layer, e);
+        if (s < 0) return fail(ODMOE_EBUSY, "all %d slots are occupied", h->cfg.n_slots);
+        if ((rc = enqueue_load(h, layer, e, s))) {
+          h->pool->release(s);
+          return rc;
+        }
+      }
+      HIP_TRY(hipStreamWaitEvent(h->compute, h->ready_ev[s], 0));
+      HIP_TRY(prefill_gemms(h->compute, h->sh, nullptr, 0, h->pool_mem + (size_t)s * h->expert_bytes,
+                            tile_first, tiles_e, x_dev, n_tokens, h->prefill_ws));
+      if ((rc = mark_used(h, s))) return rc;
+      if (evict_after) h->pool->release(s);
+      tile_first += tiles_e;
+    }
+    HIP_TRY(prefill_combine(h->compute, h->sh, gate_dev, n_tokens, y_dev, h->prefill_ws));
+    return ODMOE_OK;
+  }
+
+  // cacheless decode
+  if (n_tokens != 1) return fail(ODMOE_EINVAL, "cacheless mode computes one token, or a batch of >= 16, per call");
   int32_t ids[ODMOE_MAX_TOPK];
   if (idx_host) {
     memcpy(ids, idx_host, k * sizeof(int32_t));

@@ -127,6 +127,8 @@ struct GemmArgs {
   int slot_div;
   const void* const* table;   // expert base pointers
   int table_off;
+  const void* expert_override;  // when set: the weights of every chunk of this launch (one expert)
+  int tile_first;               // first chunk-list entry of this launch
   size_t b_off[2];            // element offsets of the two 64-row halves' matrix starts
   int b_row[2];               // first weight row of each half relative to n0
   const int32_t* offsets;
@@ -168,7 +170,8 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
     const int src_row = g.a_slot ? g.a_slot[p] / g.slot_div : p;
     a_src[i] = g.A + (size_t)src_row * g.lda + k_begin + piece * 8;
   }
-  const bf16_t* wbase = static_cast<const bf16_t*>(g.table[g.table_off + e]);
+  const bf16_t* wbase =
+      static_cast<const bf16_t*>(g.expert_override ? g.expert_override : g.table[g.table_off + e]);
   const bf16_t* b_src[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
@@ -269,10 +272,11 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
 template <bool SILU>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  if ((int)blockIdx.x >= *g.n_tiles) return;
-  const int e = g.tiles[3 * blockIdx.x];
-  const int row_lo = g.offsets[e] + g.tiles[3 * blockIdx.x + 1];
-  const int nrows = g.tiles[3 * blockIdx.x + 2];
+  const int tile = g.tile_first + (int)blockIdx.x;
+  if (tile >= *g.n_tiles) return;
+  const int e = g.tiles[3 * tile];
+  const int row_lo = g.offsets[e] + g.tiles[3 * tile + 1];
+  const int nrows = g.tiles[3 * tile + 2];
   if (nrows <= 64)
     gemm_chunk<SILU, 1, 6>(g, smem, e, row_lo, nrows);
   else if (nrows <= 128)
@@ -344,65 +348,106 @@ bool prefill_supported(const Shape& sh) {
 
 size_t prefill_workspace_bytes(const Shape& sh, int32_t T) { return carve(sh, T, nullptr).total; }
 
-hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* table, int32_t table_off,
-                          const int32_t* idx, const float* gate, const void* x, int32_t T, void* y,
-                          void* workspace, size_t workspace_bytes) {
+int prefill_chunks_of(int32_t count) {
+  if (count <= 0) return 0;
+  const int nch = (count + BMX - 1) / BMX;
+  const int per = ((count + nch - 1) / nch + 31) & ~31;
+  return (count + per - 1) / per;
+}
+
+namespace {
+
+hipError_t ensure_attrs() {
+  static bool attr_set = false;
+  if (attr_set) return hipSuccess;
+  hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<true>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
+  if (ea != hipSuccess) return ea;
+  ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<false>),
+                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
+  if (ea != hipSuccess) return ea;
+  attr_set = true;
+  return hipSuccess;
+}
+
+// K split of the w2 GEMM: few output tiles but a long K, so K is cut until the grid fills the chip.
+void w2_split(const Shape& sh, int* n_split, int* k_per_split) {
+  const int nt2 = (sh.H + BN - 1) / BN;
+  const int ksteps = sh.F / BK;
+  int ns = (4 * 256 + nt2 * 8 - 1) / (nt2 * 8);   // aim for >= 1024 blocks at ~8 chunks
+  if (ns > MAX_KSPLIT) ns = MAX_KSPLIT;
+  if (ns > ksteps) ns = ksteps;
+  if (ns < 1) ns = 1;
+  *k_per_split = ((ksteps + ns - 1) / ns) * BK;
+  *n_split = (sh.F + *k_per_split - 1) / *k_per_split;
+}
+
+}  // namespace
+
+hipError_t prefill_sort(hipStream_t s, const Shape& sh, const int32_t* idx, int32_t T, void* workspace,
+                        size_t workspace_bytes) {
   if (!prefill_supported(sh)) return hipErrorNotSupported;
-  if (T <= 0) return hipSuccess;
   const Carve c = carve(sh, T, workspace);
   if (!workspace || c.total > workspace_bytes) return hipErrorInvalidValue;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<true>),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
-    if (ea != hipSuccess) return ea;
-    ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<false>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
-    if (ea != hipSuccess) return ea;
-    attr_set = true;
-  }
-  const int n = T * sh.k;
-  const int max_tiles = sh.E + (n + BMX - 1) / BMX;
-  const size_t hf = (size_t)sh.H * sh.F;
-
-  sort_slots_kernel<<<1, 1024, 0, s>>>(idx, n, sh.E, c.offsets, c.perm, c.inv, c.tiles, c.n_tiles);
-  hipError_t e = hipGetLastError();
+  hipError_t e = ensure_attrs();
   if (e != hipSuccess) return e;
+  sort_slots_kernel<<<1, 1024, 0, s>>>(idx, T * sh.k, sh.E, c.offsets, c.perm, c.inv, c.tiles, c.n_tiles);
+  return hipGetLastError();
+}
+
+hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* table, int32_t table_off,
+                         const void* expert_override, int32_t tile_first, int32_t tile_count,
+                         const void* x, int32_t T, void* workspace) {
+  if (tile_count <= 0) return hipSuccess;
+  const Carve c = carve(sh, T, workspace);
+  const int n = T * sh.k;
+  const size_t hf = (size_t)sh.H * sh.F;
 
   GemmArgs g1{};
   g1.A = static_cast<const bf16_t*>(x); g1.lda = sh.H; g1.a_slot = c.perm; g1.slot_div = sh.k;
-  g1.table = table; g1.table_off = table_off;
+  g1.table = table; g1.table_off = table_off; g1.expert_override = expert_override; g1.tile_first = tile_first;
   g1.b_off[0] = 0; g1.b_off[1] = hf; g1.b_row[0] = 0; g1.b_row[1] = 0;        // W1 and W3 rows n0..n0+63
   g1.offsets = c.offsets; g1.tiles = c.tiles; g1.n_tiles = c.n_tiles;
   g1.out = c.hbuf; g1.ldo = sh.F; g1.N = sh.F; g1.K = sh.H; g1.k_per_split = sh.H; g1.split_stride = 0;
-  dim3 grid1(max_tiles, (sh.F + BN / 2 - 1) / (BN / 2), 1);
+  dim3 grid1(tile_count, (sh.F + BN / 2 - 1) / (BN / 2), 1);
   grouped_gemm_kernel<true><<<grid1, GEMM_THREADS, GEMM_LDS, s>>>(g1);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
 
-  // w2 GEMM: few output tiles but a long K; split K so that the grid fills the chip.
-  const int nt2 = (sh.H + BN - 1) / BN;
-  const int ksteps = sh.F / BK;
-  int n_split = (4 * 256 + nt2 * 8 - 1) / (nt2 * 8);   // aim for >= 1024 blocks at ~8 chunks
-  if (n_split > MAX_KSPLIT) n_split = MAX_KSPLIT;
-  if (n_split > ksteps) n_split = ksteps;
-  if (n_split < 1) n_split = 1;
-  const int k_per_split = ((ksteps + n_split - 1) / n_split) * BK;
-  n_split = (sh.F + k_per_split - 1) / k_per_split;
-  const size_t split_stride = (size_t)n * sh.H;
+  int n_split, k_per_split;
+  w2_split(sh, &n_split, &k_per_split);
   GemmArgs g2{};
   g2.A = c.hbuf; g2.lda = sh.F; g2.a_slot = nullptr; g2.slot_div = 1;
-  g2.table = table; g2.table_off = table_off;
+  g2.table = table; g2.table_off = table_off; g2.expert_override = expert_override; g2.tile_first = tile_first;
   g2.b_off[0] = 2 * hf; g2.b_off[1] = 2 * hf; g2.b_row[0] = 0; g2.b_row[1] = 64;  // W2 rows n0..n0+127
   g2.offsets = c.offsets; g2.tiles = c.tiles; g2.n_tiles = c.n_tiles;
   g2.out = c.ybuf; g2.ldo = sh.H; g2.N = sh.H; g2.K = sh.F; g2.k_per_split = k_per_split;
-  g2.split_stride = split_stride;
-  dim3 grid2(max_tiles, nt2, n_split);
+  g2.split_stride = (size_t)n * sh.H;
+  dim3 grid2(tile_count, (sh.H + BN - 1) / BN, n_split);
   grouped_gemm_kernel<false><<<grid2, GEMM_THREADS, GEMM_LDS, s>>>(g2);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-
-  combine_kernel<<<T, 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split,
-                                   split_stride);
   return hipGetLastError();
+}
+
+hipError_t prefill_combine(hipStream_t s, const Shape& sh, const float* gate, int32_t T, void* y,
+                           void* workspace) {
+  const Carve c = carve(sh, T, workspace);
+  int n_split, k_per_split;
+  w2_split(sh, &n_split, &k_per_split);
+  combine_kernel<<<T, 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split,
+                                   (size_t)T * sh.k * sh.H);
+  return hipGetLastError();
+}
+
+hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* table, int32_t table_off,
+                          const int32_t* idx, const float* gate, const void* x, int32_t T, void* y,
+                          void* workspace, size_t workspace_bytes) {
+  if (T <= 0) return hipSuccess;
+  hipError_t e = prefill_sort(s, sh, idx, T, workspace, workspace_bytes);
+  if (e != hipSuccess) return e;
+  const int max_tiles = sh.E + (T * sh.k + BMX - 1) / BMX;
+  e = prefill_gemms(s, sh, table, table_off, nullptr, 0, max_tiles, x, T, workspace);
+  if (e != hipSuccess) return e;
+  return prefill_combine(s, sh, gate, T, y, workspace);
 }
 
 }  // namespace odmoe

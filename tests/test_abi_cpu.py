@@ -58,3 +58,14 @@ def test_argument_errors_need_no_gpu():
     assert lib.odmoe_route_topk(None, 0, None, 1, None, None) == B.ODMOE_EINVAL
     assert lib.odmoe_decode_step(None, None, None, None, None, None) == B.ODMOE_EINVAL
     assert lib.odmoe_layer_destroy(None) == B.ODMOE_OK
+
+
+def test_load_window_matches_oracle_and_worked_example():
+    """Host-only arithmetic of the library against the oracle's reading of the load-window equation."""
+    from oracle import moe_oracle as O
+    from paper_2512_03927_amd import binding as B
+    for ng, tm, tw in [(4, 1.7, 0.9), (2, 0.01, 0.12), (1, 3.0, 5.0), (6, 0.0, 1.0)]:
+        assert abs(B.odmoe_load_window_ms(ng, tm, tw) - O.t_maxload(ng, tm, tw)) < 1e-12
+    assert abs(B.odmoe_load_window_ms(4, 1.0, 1.0) - 7.0) < 1e-12        # 4 t^M + 3 t^W
+    assert B.odmoe_load_window_ms(0, 1.0, 1.0) == 0.0
+    assert B.odmoe_slot_groups(None) == 0

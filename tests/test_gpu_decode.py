@@ -220,6 +220,37 @@ def test_hints_change_timing_only(H):
             assert s4.t_route_ms > 0 and s4.t_glue_ms > 0
 
 
+def test_hint_recall_is_what_was_planted(H):
+    """Hints corrupted at a chosen rate: the output never changes, and the confirmed fraction
+    (the paper's recall, Section 3.2) is exactly the fraction of hints left intact."""
+    from paper_2512_03927_amd import binding as B
+    cfg = synth.MoEConfig("t", 128, 256, 8, 2, n_layers=16, n_slots=4, dtype="bf16", n_tokens=3, glue=1, seed=17)
+    layers = _stack_layers(cfg)
+    X = synth.tokens(cfg)
+    L, k, E = cfg.n_layers, cfg.top_k, cfg.n_experts
+    r = np.random.default_rng(0)
+    with H.MoEStack(cfg, layers) as st:
+        assert B.odmoe_slot_groups(st.handle) == 2
+        for t in range(cfg.n_tokens):
+            x = H.to_device(X[t])
+            y0, idx0, _ = st.decode(x)
+            for rate in (0.0, 0.25, 0.75):
+                pred = idx0.copy()
+                n_bad = 0
+                for l in range(L):
+                    for i in range(k):
+                        if r.random() < rate:
+                            pred[l, i] = [e for e in range(E) if e not in idx0[l] and e not in pred[l]][0]
+                            n_bad += 1
+                y, idx, s = st.decode(x, pred=pred)
+                assert np.array_equal(H.from_device(y), H.from_device(y0)) and np.array_equal(idx, idx0)
+                assert s.hint_hits == L * k - n_bad and s.reloads == n_bad
+                assert s.loads == L * k + n_bad
+                recall = O.recall(np.array([[[O.correct_predictions(pred[l], idx0[l]) for l in range(L)]]]),
+                                  np.ones((1, 1)), k)
+                assert abs(recall - s.hint_hits / (L * k)) < 1e-12
+
+
 def test_error_paths(H):
     from paper_2512_03927_amd import binding as B
     cfg = synth.MoEConfig("t", 64, 64, 4, 2, n_layers=2, n_slots=2, dtype="f32", n_tokens=1, glue=1)

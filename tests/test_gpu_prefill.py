@@ -125,3 +125,34 @@ def test_cfg4_full_size_prefill_sampled_tokens(H):
             a, r = O.widen(yn[sl]), O.widen(y1)
             worst = max(worst, float(np.max(np.abs(a - r) / np.max(np.abs(r), axis=1, keepdims=True))))
         assert worst <= 1e-2, worst
+
+
+def test_cacheless_prefill_streams_each_expert_once_and_matches_resident(H):
+    """Prefill with the experts in pinned host memory and only 2 HBM slots: each expert that got
+    tokens is copied once, results are bit-identical to the resident prefill and match the oracle."""
+    from paper_2512_03927_amd import binding as B
+    cfg = synth.MoEConfig("t", 256, 512, 8, 2, dtype="bf16", n_tokens=300, router_bias=True, seed=31)
+    Wg, b, experts = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Y, IDX, _ = O.moe_layer_tokens(X, Wg, b, experts, cfg.top_k)
+    with H.MoEStack(cfg, [(Wg, b, experts)]) as res:
+        x = H.to_device(X)
+        idx, gate = res.route(0, x)
+        y_res = H.from_device(res.ffn(0, idx, gate, x))
+    for n_slots, idx_host in ((2, None), (3, np.ascontiguousarray(IDX))):
+        ccfg = cfg.small(n_slots=n_slots)
+        with H.MoEStack(ccfg, [(Wg, b, experts)]) as st:
+            x = H.to_device(X)
+            idx, gate = st.route(0, x)
+            assert np.array_equal(idx.cpu().numpy(), IDX)
+            y = H.from_device(st.ffn(0, idx, gate, x, idx_host=idx_host, evict_after=1))
+            assert np.array_equal(y, y_res)
+            _check_tokens(y, Y, range(0, cfg.n_tokens, 7))
+            # everything was evicted: a second call loads again and gives the same bits
+            y2 = H.from_device(st.ffn(0, idx, gate, x, idx_host=idx_host, evict_after=1))
+            assert np.array_equal(y2, y_res)
+            # a decode token on the same handle still works afterwards
+            yt, idx_t, stats = st.decode(x[5])
+            assert np.array_equal(idx_t[0], IDX[5]) and stats.loads == cfg.top_k
+            with pytest.raises(B.OdmoeError):                      # 1 < n_tokens < 16 is not served here
+                st.ffn(0, idx[:4].contiguous(), gate[:4].contiguous(), x[:4].contiguous())
