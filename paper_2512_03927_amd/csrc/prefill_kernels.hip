@@ -16,8 +16,8 @@ namespace odmoe {
 namespace {
 
 constexpr int BMX = 256;     // most rows of one expert a block takes (one "chunk")
-constexpr int BN = 128;      // weight rows per block tile: two 64-row halves (W1 and W3 rows of the
-                             // same 64 ffn columns for the first GEMM, 128 consecutive rows for the second)
+constexpr int BN = 256;      // weight rows per block tile: two 128-row halves (W1 and W3 rows of the
+                             // same 128 ffn columns for the first GEMM, 256 consecutive rows for the second)
 constexpr int BK = 64;       // K elements per pipeline step (one 128-byte line per row)
 constexpr int GEMM_THREADS = 512;
 constexpr int MAX_KSPLIT = 8;
@@ -99,16 +99,19 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //   - global memory goes straight into LDS (global_load_lds_dwordx4: a wave fills 1 KB = 8 rows of
 //     128 bytes per instruction, every 128-byte line fully coalesced) in a ring of K-steps of
 //     BK = 64; no staging registers, one s_barrier per step, and the only vmcnt wait is for the
-//     step about to be used.  The ring is as deep as 144 KB of LDS allow for the chunk's rows:
-//     6 steps for up to 64 rows, 4 for up to 128, 3 for up to 256 - small chunks do little
-//     arithmetic per step, so they need more weight bytes in flight to cover HBM latency;
+//     step about to be used.  The ring holds 3 steps of 40 / 48 KB for up to 64 / 128 rows and 2
+//     steps of 64 KB for up to 256 rows (measured: a fourth step does not help; reading the
+//     row-major weights 128 bytes per row at a time caps the stream at about 5.4 TB/s, against
+//     6.4 TB/s for whole rows);
 //   - LDS rows are 128 bytes; the 16-byte piece q of row r sits at slot q ^ (r & 7) (the lane
 //     that fills slot s of row r fetches piece s ^ (r & 7)), so the MFMA fragment reads are
 //     conflict-free;
-//   - 8 waves as 4 (M, 64 rows) x 2 (N, 32 columns of each 64-row half); 32-row tiles past the
-//     end of the chunk are skipped.
-//   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+63; out = bf16( silu(A W1^T) * (A W3^T) )
-//   !SILU : halves = weight rows n0..n0+63 / n0+64..n0+127; out = fp32 partial sums for K range
+//   - 8 waves as 2 (M) x 4 (N, 32 columns of each 128-row half); a wave multiplies up to four
+//     32-row tiles by its two 32-column tiles (8 MFMAs per 6 fragment reads), which keeps LDS
+//     read traffic below MFMA time; 32-row tiles past the end of the chunk are skipped;
+//   - the 128-column-wide block tile also halves the activation traffic per weight byte.
+//   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+127; out = bf16( silu(A W1^T) * (A W3^T) )
+//   !SILU : halves = weight rows n0..n0+127 / n0+128..n0+255; out = fp32 partial sums for K range
 //           blockIdx.z, [gridDim.z][rows, ldo]
 // grid: x = entry of the chunk list, y = N tile, z = K split.  K is a multiple of 64.
 // ---------------------------------------------------------------------------------------------
@@ -141,8 +144,10 @@ struct GemmArgs {
 
 template <bool SILU, int A_INSTR, int NSTAGE>
 __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int e, int row_lo, int nrows) {
-  constexpr int A_ROWS = 64 * A_INSTR;
-  constexpr int LPS = A_INSTR + 2;                      // DMA loads per wave per K-step
+  constexpr int A_ROWS = 64 * A_INSTR;                  // 64, 128 or 256 rows of activations staged
+  constexpr int MTW = A_ROWS / 64;                      // 32-row tiles per wave (two M halves)
+  constexpr int B_INSTR = BN / 64;                      // B fills per wave per K-step
+  constexpr int LPS = A_INSTR + B_INSTR;                // DMA loads per wave per K-step
   constexpr size_t A_STAGE = (size_t)A_ROWS * BK;
   constexpr size_t STAGE = A_STAGE + (size_t)BN * BK;
   static_assert(NSTAGE * STAGE * sizeof(bf16_t) <= GEMM_LDS, "ring does not fit");
@@ -151,7 +156,7 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   const int n0 = blockIdx.y * (SILU ? BN / 2 : BN);
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave >> 2, wn = wave & 3;
   const int K = g.K;
   const int k_begin = blockIdx.z * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split < K) ? k_begin + g.k_per_split : K;
@@ -172,12 +177,14 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   }
   const bf16_t* wbase =
       static_cast<const bf16_t*>(g.expert_override ? g.expert_override : g.table[g.table_off + e]);
-  const bf16_t* b_src[2];
+  const bf16_t* b_src[B_INSTR];                         // LDS rows (i*8 + wave)*8 + sub of the B tile
 #pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    int n = n0 + g.b_row[b] + wave * 8 + sub;
+  for (int i = 0; i < B_INSTR; ++i) {
+    const int br = (i * 8 + wave) * 8 + sub;            // 0..255: half = br / 128, row in half = br % 128
+    const int half = br >> 7;
+    int n = n0 + g.b_row[half] + (br & 127);
     n = n < g.N ? n : g.N - 1;                          // rows past N: any valid row (never stored)
-    b_src[b] = wbase + g.b_off[b] + (size_t)n * K + k_begin + piece * 8;
+    b_src[i] = wbase + g.b_off[half] + (size_t)n * K + k_begin + piece * 8;
   }
   auto issue = [&](int stage, int kt) {
     bf16_t* sa = smem + stage * STAGE;
@@ -187,21 +194,24 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
       __builtin_amdgcn_global_load_lds((global_void_ptr)(a_src[i] + ko),
                                        (lds_void_ptr)(sa + (i * 8 + wave) * 8 * BK), 16, 0, 0);
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(b_src[b] + ko),
-                                       (lds_void_ptr)(sa + A_STAGE + (b * 64 + wave * 8) * BK), 16, 0, 0);
+    for (int i = 0; i < B_INSTR; ++i)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(b_src[i] + ko),
+                                       (lds_void_ptr)(sa + A_STAGE + (i * 8 + wave) * 8 * BK), 16, 0, 0);
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[MTW][2];
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+  for (int mt = 0; mt < MTW; ++mt)
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][b][i] = 0.f;
 
   const int fr = lane & 31, fg = lane >> 5;            // fragment row within a 32-tile, K half
-  const bool mt_on[2] = {wm * 64 < nrows, wm * 64 + 32 < nrows};
+  const int m_base = wm * (A_ROWS / 2);                // this wave's first row
+  bool mt_on[MTW];
+#pragma unroll
+  for (int mt = 0; mt < MTW; ++mt) mt_on[mt] = m_base + mt * 32 < nrows;
 
   const int last = nk - 1;
 #pragma unroll
@@ -221,16 +231,15 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
         bf16x8 bfrag[2];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-          bfrag[b] = *reinterpret_cast<const bf16x8*>(sb + lds_slot(b * 64 + wn * 32 + fr, pc));
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(sa + lds_slot(wm * 64 + fr, pc));
+          bfrag[b] = *reinterpret_cast<const bf16x8*>(sb + lds_slot(b * 128 + wn * 32 + fr, pc));
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-          acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, bfrag[b], acc[0][b], 0, 0, 0);
-        if (mt_on[1]) {
-          const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(sa + lds_slot(wm * 64 + 32 + fr, pc));
+        for (int mt = 0; mt < MTW; ++mt) {
+          if (mt == 0 || mt_on[mt]) {
+            const bf16x8 af = *reinterpret_cast<const bf16x8*>(sa + lds_slot(m_base + mt * 32 + fr, pc));
 #pragma unroll
-          for (int b = 0; b < 2; ++b)
-            acc[1][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, bfrag[b], acc[1][b], 0, 0, 0);
+            for (int b = 0; b < 2; ++b)
+              acc[mt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfrag[b], acc[mt][b], 0, 0, 0);
+          }
         }
       }
     }
@@ -241,11 +250,11 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
 
   // ---- epilogue.  Accumulator layout: column = lane % 32, row = (i/4)*8 + (lane/32)*4 + i%4.
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
+  for (int mt = 0; mt < MTW; ++mt) {
     if (!mt_on[mt]) continue;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int m = wm * 64 + mt * 32 + (i >> 2) * 8 + fg * 4 + (i & 3);
+      const int m = m_base + mt * 32 + (i >> 2) * 8 + fg * 4 + (i & 3);
       if (m < nrows) {
         const size_t p = (size_t)(row_lo + m);
         if constexpr (SILU) {
@@ -258,7 +267,7 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
         } else {
 #pragma unroll
           for (int b = 0; b < 2; ++b) {
-            const int col = n0 + b * 64 + wn * 32 + fr;
+            const int col = n0 + b * 128 + wn * 32 + fr;
             if (col < g.N)
               ((__attribute__((address_space(1))) float*)g.out)[blockIdx.z * g.split_stride + p * g.ldo + col] =
                   acc[mt][b][i];
@@ -278,11 +287,11 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) 
   const int row_lo = g.offsets[e] + g.tiles[3 * tile + 1];
   const int nrows = g.tiles[3 * tile + 2];
   if (nrows <= 64)
-    gemm_chunk<SILU, 1, 6>(g, smem, e, row_lo, nrows);
+    gemm_chunk<SILU, 1, 3>(g, smem, e, row_lo, nrows);
   else if (nrows <= 128)
-    gemm_chunk<SILU, 2, 4>(g, smem, e, row_lo, nrows);
+    gemm_chunk<SILU, 2, 3>(g, smem, e, row_lo, nrows);
   else
-    gemm_chunk<SILU, 4, 3>(g, smem, e, row_lo, nrows);
+    gemm_chunk<SILU, 4, 2>(g, smem, e, row_lo, nrows);
 }
 
 // Y[t, :] = sum_i gate[t,i] * (sum_z Ybuf[z][inv[t*k+i], :]), rounded once to bf16.  One block
@@ -406,7 +415,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   GemmArgs g1{};
   g1.A = static_cast<const bf16_t*>(x); g1.lda = sh.H; g1.a_slot = c.perm; g1.slot_div = sh.k;
   g1.table = table; g1.table_off = table_off; g1.expert_override = expert_override; g1.tile_first = tile_first;
-  g1.b_off[0] = 0; g1.b_off[1] = hf; g1.b_row[0] = 0; g1.b_row[1] = 0;        // W1 and W3 rows n0..n0+63
+  g1.b_off[0] = 0; g1.b_off[1] = hf; g1.b_row[0] = 0; g1.b_row[1] = 0;        // W1 and W3 rows n0..n0+127
   g1.offsets = c.offsets; g1.tiles = c.tiles; g1.n_tiles = c.n_tiles;
   g1.out = c.hbuf; g1.ldo = sh.F; g1.N = sh.F; g1.K = sh.H; g1.k_per_split = sh.H; g1.split_stride = 0;
   dim3 grid1(tile_count, (sh.F + BN / 2 - 1) / (BN / 2), 1);
@@ -419,7 +428,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   GemmArgs g2{};
   g2.A = c.hbuf; g2.lda = sh.F; g2.a_slot = nullptr; g2.slot_div = 1;
   g2.table = table; g2.table_off = table_off; g2.expert_override = expert_override; g2.tile_first = tile_first;
-  g2.b_off[0] = 2 * hf; g2.b_off[1] = 2 * hf; g2.b_row[0] = 0; g2.b_row[1] = 64;  // W2 rows n0..n0+127
+  g2.b_off[0] = 2 * hf; g2.b_off[1] = 2 * hf; g2.b_row[0] = 0; g2.b_row[1] = 128;  // W2 rows n0..n0+255
   g2.offsets = c.offsets; g2.tiles = c.tiles; g2.n_tiles = c.n_tiles;
   g2.out = c.ybuf; g2.ldo = sh.H; g2.N = sh.H; g2.K = sh.F; g2.k_per_split = k_per_split;
   g2.split_stride = (size_t)n * sh.H;
