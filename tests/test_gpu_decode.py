@@ -77,6 +77,8 @@ SHAPES = [
     (64, 32776, 3, 2, "f32"),       # F beyond the register-resident w2 kernel -> LDS-staged fallback
     (8200, 72, 4, 2, "bf16"),       # bf16 H just past 16 chunks -> fallback
     (4096, 14336, 8, 2, "bf16"),    # the Mixtral layer shape (configs 2-4)
+    (64, 64, 1024, 8, "bf16"),      # the most experts and the largest top-k the library takes
+    (64, 64, 1, 1, "f32"),          # a single expert
 ]
 
 
