@@ -2,8 +2,9 @@
 // SiLU gate and the weighted combine, and the inter-layer glue.
 //
 // The expert GEMVs are bound by HBM bandwidth (one multiply-add per weight element, every weight
-// read exactly once per token), so they use 128-bit non-temporal loads, keep the input vector in
-// LDS as fp32 and never touch the matrix cores.
+// read exactly once per token), so they stream the weights with 128-bit non-temporal loads,
+// keep the input vector slice in registers (in LDS for shapes too large for that) and never
+// touch the matrix cores.
 #include "kernels.h"
 
 namespace odmoe {
