@@ -20,6 +20,7 @@ Also reported on the same JSON line:
 from __future__ import annotations
 
 import argparse
+import contextlib
 import json
 import os
 import sys
@@ -48,6 +49,8 @@ def main() -> int:
     ap.add_argument("--prefill-iters", type=int, default=5, help="timed prefill calls of 512 tokens (0 = skip)")
     ap.add_argument("--probe-mib", type=int, default=672,
                     help="size of the plain read/copy probe that measures the HBM and host-link ceilings (0 = skip)")
+    ap.add_argument("--no-prefill-from-host", action="store_true",
+                    help="skip the prefill run that streams the experts from host memory")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -193,7 +196,10 @@ def main() -> int:
         # the same batch with the experts in pinned host memory and 4 HBM slots (Section 3.3 on one GPU:
         # every expert is streamed in once; its GEMMs overlap the next expert's copy)
         c4h = c4.small(n_slots=4)
-        with harness.MoEStack(c4h, [(Wg4, b4, experts4)]) as st4h:
+        if args.no_prefill_from_host:
+            c4h = None
+        with (harness.MoEStack(c4h, [(Wg4, b4, experts4)]) if c4h else contextlib.nullcontext()) as st4h:
+          if c4h:
             idx4h, gate4h = st4h.route(0, X4)
             ih = idx4h.cpu().numpy()
             Y4h = torch.empty_like(X4)
@@ -205,9 +211,9 @@ def main() -> int:
             torch.cuda.synchronize()
             ms_h = (time.perf_counter() - t1) / 2 * 1e3
             same = bool(torch.equal(Y4h, Y4))
-        prefill["from_host"] = {"ms": round(ms_h, 3), "h2d_GBps": round(wbytes / (ms_h * 1e-3) / 1e9, 2),
-                                "n_slots": 4, "experts_loaded": int(np.count_nonzero(counts)),
-                                "bit_identical_to_resident": same}
+            prefill["from_host"] = {"ms": round(ms_h, 3), "h2d_GBps": round(wbytes / (ms_h * 1e-3) / 1e9, 2),
+                                    "n_slots": 4, "experts_loaded": int(np.count_nonzero(counts)),
+                                    "bit_identical_to_resident": same}
         log(f"[bench] prefill: {prefill}")
 
     # ---- cacheless stacks, short runs (host-link roofline)
