@@ -49,6 +49,8 @@ def main() -> int:
     ap.add_argument("--prefill-iters", type=int, default=5, help="timed prefill calls of 512 tokens (0 = skip)")
     ap.add_argument("--probe-mib", type=int, default=672,
                     help="size of the plain read/copy probe that measures the HBM and host-link ceilings (0 = skip)")
+    ap.add_argument("--sep-iters", type=int, default=32,
+                    help="emulated decode iterations with a quantised shadow stack supplying hints (0 = skip)")
     ap.add_argument("--no-prefill-from-host", action="store_true",
                     help="skip the prefill run that streams the experts from host memory")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
@@ -278,6 +280,24 @@ def main() -> int:
         X5 = synth.tokens(c5, 4)
         cacheless_fine = run_cacheless(c5, layers5, 8 * args.cacheless_tokens, [X5[t] for t in range(4)])
 
+    # ---- emulated SEP predictor: a quantised shadow stack supplies the hints (qualitative only)
+    sep = None
+    if args.sep_iters > 0:
+        from paper_2512_03927_amd import shadow
+        cs = synth.MoEConfig("sep-h1024-f2048-e8-k2-16L", 1024, 2048, 8, 2, n_layers=16, n_slots=4,
+                             dtype="bf16", n_tokens=1, glue=1, seed=7)
+        layers_s = [synth.layer_weights(cs, l) for l in range(cs.n_layers)]
+        xs0 = harness.to_device(synth.tokens(cs)[0])
+        sep = {"workload": cs.name, "iterations": args.sep_iters, "mean_recall": {}}
+        with harness.MoEStack(cs, layers_s) as main_s:
+            for kind in ("bf16", "int8", "int4"):
+                with harness.MoEStack(cs.small(n_slots=0), shadow.shadow_layers(cs, layers_s, kind)) as sh:
+                    for aligned in (True, False):
+                        r, _ = shadow.emulate(main_s, sh, xs0, args.sep_iters, aligned)
+                        sep["mean_recall"][f"{kind}_{'aligned' if aligned else 'unaligned'}"] = round(float(np.mean(r)), 4)
+        sep["random_prefetch_expectation"] = cs.top_k / cs.n_experts
+        log(f"[bench] sep emulation: {sep}")
+
     # ---- CPU oracle on a bounded sample of the same workload
     cpu = None
     if args.cpu_tokens > 0:
@@ -311,7 +331,7 @@ def main() -> int:
         "expert_gemv_hbm_GBps": None if gemv_gbps is None else round(gemv_gbps, 1),
         "measured_ceilings": ceilings,
         "roofline": roofline, "cacheless": cacheless, "cacheless_fine_grained": cacheless_fine,
-        "prefill": prefill, "cpu_baseline": cpu,
+        "prefill": prefill, "sep_emulation": sep, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
     return 0
