@@ -21,6 +21,7 @@ constexpr int BN = 256;      // weight rows per block tile: two 128-row halves (
 constexpr int BK = 64;       // K elements per pipeline step (one 128-byte line per row)
 constexpr int GEMM_THREADS = 512;
 constexpr int MAX_KSPLIT = 8;
+constexpr unsigned K_ROTATE = 24;  // K-steps between the starting points of neighbouring N tiles
 constexpr size_t GEMM_LDS = 144 * 1024;  // the LDS ring; its depth depends on the rows of the chunk
 
 typedef uint16_t bf16_t;
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+127; out = bf16( silu(A W1^T) * (A W3^T) )
 //   !SILU : halves = weight rows n0..n0+127 / n0+128..n0+255; out = fp32 partial sums for K range
 //           blockIdx.z, [gridDim.z][rows, ldo]
-// grid: x = entry of the chunk list, y = N tile, z = K split.  K is a multiple of 64.
+// grid: x = N tile, y = entry of the chunk list, z = K split.  K is a multiple of 64.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_slot(int row, int piece) { return row * BK + ((piece ^ (row & 7)) << 3); }
 
@@ -142,10 +143,11 @@ struct GemmArgs {
   size_t split_stride;
 };
 
-template <bool SILU, int A_INSTR, int NSTAGE>
+template <bool SILU, int NT, int NSTAGE>
 __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int e, int row_lo, int nrows) {
-  constexpr int A_ROWS = 64 * A_INSTR;                  // 64, 128 or 256 rows of activations staged
-  constexpr int MTW = A_ROWS / 64;                      // 32-row tiles per wave (two M halves)
+  constexpr int A_INSTR = (NT + 1) / 2;                 // A fills per wave per K-step (64 rows each)
+  constexpr int A_ROWS = 64 * A_INSTR;                  // rows of activations staged (NT 32-row tiles used)
+  constexpr int MTW = (NT + 1) / 2;                     // 32-row tiles per wave: tiles wm, wm+2, wm+4, ...
   constexpr int B_INSTR = BN / 64;                      // B fills per wave per K-step
   constexpr int LPS = A_INSTR + B_INSTR;                // DMA loads per wave per K-step
   constexpr size_t A_STAGE = (size_t)A_ROWS * BK;
@@ -153,7 +155,8 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   static_assert(NSTAGE * STAGE * sizeof(bf16_t) <= GEMM_LDS, "ring does not fit");
   static_assert((NSTAGE - 2) * LPS < 64, "vmcnt is 6 bits");
 
-  const int n0 = blockIdx.y * (SILU ? BN / 2 : BN);
+  const int n0 = blockIdx.x * (SILU ? BN / 2 : BN);
+  if (n0 >= g.N) return;                                // grid.x is padded to a multiple of 8
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
@@ -186,9 +189,15 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
     n = n < g.N ? n : g.N - 1;                          // rows past N: any valid row (never stored)
     b_src[i] = wbase + g.b_off[half] + (size_t)n * K + k_begin + piece * 8;
   }
+  // Blocks that run side by side start their K loops at different steps: rows of a row-major
+  // matrix lie a multiple of 4 KB apart, so blocks marching through K in lockstep would keep
+  // hitting the same memory channels.
+  const int kt0 = (int)((blockIdx.x * K_ROTATE + blockIdx.z * 7u) % (unsigned)nk);
   auto issue = [&](int stage, int kt) {
     bf16_t* sa = smem + stage * STAGE;
-    const int ko = kt * BK;
+    int kr = kt + kt0;
+    kr = kr >= nk ? kr - nk : kr;
+    const int ko = kr * BK;
 #pragma unroll
     for (int i = 0; i < A_INSTR; ++i)
       __builtin_amdgcn_global_load_lds((global_void_ptr)(a_src[i] + ko),
@@ -208,10 +217,8 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
       for (int i = 0; i < 16; ++i) acc[mt][b][i] = 0.f;
 
   const int fr = lane & 31, fg = lane >> 5;            // fragment row within a 32-tile, K half
-  const int m_base = wm * (A_ROWS / 2);                // this wave's first row
-  bool mt_on[MTW];
-#pragma unroll
-  for (int mt = 0; mt < MTW; ++mt) mt_on[mt] = m_base + mt * 32 < nrows;
+  // With an odd tile count the second M group of waves has one tile fewer (wave-uniform test).
+  auto tile_on = [&](int mt) { return 2 * mt + 1 < NT || wm == 0; };
 
   const int last = nk - 1;
 #pragma unroll
@@ -222,25 +229,26 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
     __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done with step kt-1
     const int nxt = kt + NSTAGE - 1;
     issue(refill, nxt < last ? nxt : last);            // refill the buffer that step kt-1 used
-    if (mt_on[0]) {
+    {
       const bf16_t* sa = smem + stage * STAGE;
       const bf16_t* sb = sa + A_STAGE;
 #pragma unroll
       for (int s = 0; s < BK / 16; ++s) {
         const int pc = 2 * s + fg;
-        bf16x8 bfrag[2];
+        bf16x8 bfrag[2], afrag[MTW];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
           bfrag[b] = *reinterpret_cast<const bf16x8*>(sb + lds_slot(b * 128 + wn * 32 + fr, pc));
 #pragma unroll
-        for (int mt = 0; mt < MTW; ++mt) {
-          if (mt == 0 || mt_on[mt]) {
-            const bf16x8 af = *reinterpret_cast<const bf16x8*>(sa + lds_slot(m_base + mt * 32 + fr, pc));
+        for (int mt = 0; mt < MTW; ++mt)
+          if (tile_on(mt)) afrag[mt] = *reinterpret_cast<const bf16x8*>(sa + lds_slot((2 * mt + wm) * 32 + fr, pc));
+#pragma unroll
+        for (int mt = 0; mt < MTW; ++mt)
+          if (tile_on(mt)) {
 #pragma unroll
             for (int b = 0; b < 2; ++b)
-              acc[mt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bfrag[b], acc[mt][b], 0, 0, 0);
+              acc[mt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mt], bfrag[b], acc[mt][b], 0, 0, 0);
           }
-        }
       }
     }
     stage = stage + 1 == NSTAGE ? 0 : stage + 1;
@@ -251,10 +259,10 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   // ---- epilogue.  Accumulator layout: column = lane % 32, row = (i/4)*8 + (lane/32)*4 + i%4.
 #pragma unroll
   for (int mt = 0; mt < MTW; ++mt) {
-    if (!mt_on[mt]) continue;
+    if (!tile_on(mt)) continue;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int m = m_base + mt * 32 + (i >> 2) * 8 + fg * 4 + (i & 3);
+      const int m = (2 * mt + wm) * 32 + (i >> 2) * 8 + fg * 4 + (i & 3);
       if (m < nrows) {
         const size_t p = (size_t)(row_lo + m);
         if constexpr (SILU) {
@@ -281,17 +289,21 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
 template <bool SILU>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  const int tile = g.tile_first + (int)blockIdx.x;
+  const int tile = g.tile_first + (int)blockIdx.y;
   if (tile >= *g.n_tiles) return;
   const int e = g.tiles[3 * tile];
   const int row_lo = g.offsets[e] + g.tiles[3 * tile + 1];
   const int nrows = g.tiles[3 * tile + 2];
-  if (nrows <= 64)
-    gemm_chunk<SILU, 1, 3>(g, smem, e, row_lo, nrows);
-  else if (nrows <= 128)
-    gemm_chunk<SILU, 2, 3>(g, smem, e, row_lo, nrows);
-  else
-    gemm_chunk<SILU, 4, 2>(g, smem, e, row_lo, nrows);
+  switch ((nrows + 31) >> 5) {      // 32-row tiles of the chunk
+    case 1: gemm_chunk<SILU, 1, 3>(g, smem, e, row_lo, nrows); break;
+    case 2: gemm_chunk<SILU, 2, 3>(g, smem, e, row_lo, nrows); break;
+    case 3: gemm_chunk<SILU, 3, 3>(g, smem, e, row_lo, nrows); break;
+    case 4: gemm_chunk<SILU, 4, 3>(g, smem, e, row_lo, nrows); break;
+    case 5: gemm_chunk<SILU, 5, 2>(g, smem, e, row_lo, nrows); break;
+    case 6: gemm_chunk<SILU, 6, 2>(g, smem, e, row_lo, nrows); break;
+    case 7: gemm_chunk<SILU, 7, 2>(g, smem, e, row_lo, nrows); break;
+    default: gemm_chunk<SILU, 8, 2>(g, smem, e, row_lo, nrows); break;
+  }
 }
 
 // Y[t, :] = sum_i gate[t,i] * (sum_z Ybuf[z][inv[t*k+i], :]), rounded once to bf16.  One block
@@ -408,6 +420,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
                          const void* expert_override, int32_t tile_first, int32_t tile_count,
                          const void* x, int32_t T, void* workspace) {
   if (tile_count <= 0) return hipSuccess;
+  if (tile_count > 65535) return hipErrorInvalidValue;  // grid.y
   const Carve c = carve(sh, T, workspace);
   const int n = T * sh.k;
   const size_t hf = (size_t)sh.H * sh.F;
@@ -418,7 +431,10 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   g1.b_off[0] = 0; g1.b_off[1] = hf; g1.b_row[0] = 0; g1.b_row[1] = 0;        // W1 and W3 rows n0..n0+127
   g1.offsets = c.offsets; g1.tiles = c.tiles; g1.n_tiles = c.n_tiles;
   g1.out = c.hbuf; g1.ldo = sh.F; g1.N = sh.F; g1.K = sh.H; g1.k_per_split = sh.H; g1.split_stride = 0;
-  dim3 grid1(tile_count, (sh.F + BN / 2 - 1) / (BN / 2), 1);
+  // x = N tile (fastest; padded to a multiple of the 8 XCDs so that the chunks of one expert that
+  // share an N tile land on the same XCD and its L2), y = chunk, z = K split.
+  auto pad8 = [](int v) { return (v + 7) & ~7; };
+  dim3 grid1(pad8((sh.F + BN / 2 - 1) / (BN / 2)), tile_count, 1);
   grouped_gemm_kernel<true><<<grid1, GEMM_THREADS, GEMM_LDS, s>>>(g1);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -432,7 +448,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   g2.offsets = c.offsets; g2.tiles = c.tiles; g2.n_tiles = c.n_tiles;
   g2.out = c.ybuf; g2.ldo = sh.H; g2.N = sh.H; g2.K = sh.F; g2.k_per_split = k_per_split;
   g2.split_stride = (size_t)n * sh.H;
-  dim3 grid2(tile_count, (sh.H + BN - 1) / BN, n_split);
+  dim3 grid2(pad8((sh.H + BN - 1) / BN), tile_count, n_split);
   grouped_gemm_kernel<false><<<grid2, GEMM_THREADS, GEMM_LDS, s>>>(g2);
   return hipGetLastError();
 }
