@@ -55,6 +55,7 @@ hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* tab
 // run both GEMMs for the chunk-list entries [tile_first, tile_first + tile_count) with the weights
 // at expert_override (or from the table when null); combine.  Chunk-list entries are ordered by
 // expert; prefill_chunks_of(count) is the number of entries of an expert with `count` token-slots.
+// A range given to prefill_gemms must hold all entries of each expert it touches.
 hipError_t prefill_sort(hipStream_t s, const Shape& sh, const int32_t* idx, int32_t T, void* workspace,
                         size_t workspace_bytes);
 hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* table, int32_t table_off,

@@ -21,6 +21,7 @@ constexpr int BN = 256;      // weight rows per block tile: two 128-row halves (
 constexpr int BK = 64;       // K elements per pipeline step (one 128-byte line per row)
 constexpr int GEMM_THREADS = 512;
 constexpr int MAX_KSPLIT = 8;
+constexpr int TILE_REC = 5;   // ints per entry of the chunk list
 constexpr unsigned K_ROTATE = 24;  // K-steps between the starting points of neighbouring N tiles
 constexpr size_t GEMM_LDS = 144 * 1024;  // the LDS ring; its depth depends on the rows of the chunk
 
@@ -40,8 +41,9 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 // ---------------------------------------------------------------------------------------------
 // Bucket the n = T*k token-slots by expert.  One block.  Slots with an out-of-range expert id
 // are left out (inv = -1) and contribute nothing.
-// tiles: (expert, first row within the expert, rows) triples, at most BMX rows each, the rows of
-// an expert split evenly over its chunks; *n_tiles their number.
+// tiles: one record of TILE_REC ints per chunk: expert, first row within the expert, rows (at most
+// BMX, the rows of an expert split evenly over its chunks), index of the expert's first chunk and
+// the number of its chunks; *n_tiles their number.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restrict__ idx, int n, int E,
                                                            int32_t* __restrict__ offsets,
@@ -64,11 +66,15 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
       start[e] = run;
       offsets[e] = run;
       const int nch = (cnt[e] + BMX - 1) / BMX;
-      const int per = nch ? (((cnt[e] + nch - 1) / nch + 31) & ~31) : 0;
+      const int per = nch ? (cnt[e] + nch - 1) / nch : 0;
+      const int first = nt;
       for (int m0 = 0; m0 < cnt[e]; m0 += per) {
-        tiles[3 * nt] = e;
-        tiles[3 * nt + 1] = m0;
-        tiles[3 * nt + 2] = (cnt[e] - m0 < per) ? cnt[e] - m0 : per;
+        int32_t* tl = tiles + TILE_REC * nt;
+        tl[0] = e;
+        tl[1] = m0;
+        tl[2] = (cnt[e] - m0 < per) ? cnt[e] - m0 : per;
+        tl[3] = first;
+        tl[4] = nch;
         ++nt;
       }
       run += cnt[e];
@@ -144,7 +150,7 @@ struct GemmArgs {
 };
 
 template <bool SILU, int NT, int NSTAGE>
-__device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int e, int row_lo, int nrows) {
+__device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int ntile, int e, int row_lo, int nrows) {
   constexpr int A_INSTR = (NT + 1) / 2;                 // A fills per wave per K-step (64 rows each)
   constexpr int A_ROWS = 64 * A_INSTR;                  // rows of activations staged (NT 32-row tiles used)
   constexpr int MTW = (NT + 1) / 2;                     // 32-row tiles per wave: tiles wm, wm+2, wm+4, ...
@@ -155,7 +161,7 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   static_assert(NSTAGE * STAGE * sizeof(bf16_t) <= GEMM_LDS, "ring does not fit");
   static_assert((NSTAGE - 2) * LPS < 64, "vmcnt is 6 bits");
 
-  const int n0 = blockIdx.x * (SILU ? BN / 2 : BN);
+  const int n0 = ntile * (SILU ? BN / 2 : BN);
   if (n0 >= g.N) return;                                // grid.x is padded to a multiple of 8
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -192,21 +198,31 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   // Blocks that run side by side start their K loops at different steps: rows of a row-major
   // matrix lie a multiple of 4 KB apart, so blocks marching through K in lockstep would keep
   // hitting the same memory channels.
-  const int kt0 = (int)((blockIdx.x * K_ROTATE + blockIdx.z * 7u) % (unsigned)nk);
-  auto issue = [&](int stage, int kt) {
-    bf16_t* sa = smem + stage * STAGE;
+  const int kt0 = (int)(((unsigned)ntile * K_ROTATE + blockIdx.z * 7u) % (unsigned)nk);
+  auto step_offset = [&](int kt) {
     int kr = kt + kt0;
     kr = kr >= nk ? kr - nk : kr;
-    const int ko = kr * BK;
+    return kr * BK;
+  };
+  auto issue_a = [&](int stage, int kt) {
+    bf16_t* sa = smem + stage * STAGE;
+    const int ko = step_offset(kt);
 #pragma unroll
     for (int i = 0; i < A_INSTR; ++i)
       __builtin_amdgcn_global_load_lds((global_void_ptr)(a_src[i] + ko),
                                        (lds_void_ptr)(sa + (i * 8 + wave) * 8 * BK), 16, 0, 0);
+  };
+  auto issue_b = [&](int stage, int kt) {
+    bf16_t* sa = smem + stage * STAGE;
+    const int ko = step_offset(kt);
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i)
       __builtin_amdgcn_global_load_lds((global_void_ptr)(b_src[i] + ko),
                                        (lds_void_ptr)(sa + A_STAGE + (i * 8 + wave) * 8 * BK), 16, 0, 0);
   };
+  // With a two-deep ring only one step is in flight: the weight fills (HBM) go out first and the
+  // activation fills (L2 hits) half a step later, which spreads the requests over the step.
+  constexpr bool SPLIT_ISSUE = NSTAGE == 2;
 
   f32x16 acc[MTW][2];
 #pragma unroll
@@ -222,19 +238,24 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
 
   const int last = nk - 1;
 #pragma unroll
-  for (int st = 0; st < NSTAGE - 1; ++st) issue(st, st < last ? st : last);
+  for (int st = 0; st < NSTAGE - 1; ++st) {
+    issue_a(st, st < last ? st : last);
+    issue_b(st, st < last ? st : last);
+  }
   int stage = 0, refill = NSTAGE - 1;
   for (int kt = 0; kt < nk; ++kt) {
     ODMOE_VMCNT((NSTAGE - 2) * LPS);   // this wave's fills of step kt have landed (later steps may fly)
     __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done with step kt-1
-    const int nxt = kt + NSTAGE - 1;
-    issue(refill, nxt < last ? nxt : last);            // refill the buffer that step kt-1 used
+    const int nxt = kt + NSTAGE - 1 < last ? kt + NSTAGE - 1 : last;
+    if (!SPLIT_ISSUE) issue_a(refill, nxt);            // refill the buffer that step kt-1 used
+    issue_b(refill, nxt);
     {
       const bf16_t* sa = smem + stage * STAGE;
       const bf16_t* sb = sa + A_STAGE;
 #pragma unroll
       for (int s = 0; s < BK / 16; ++s) {
         const int pc = 2 * s + fg;
+        if (SPLIT_ISSUE && s == BK / 32) issue_a(refill, nxt);
         bf16x8 bfrag[2], afrag[MTW];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
@@ -289,49 +310,63 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
 template <bool SILU>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  const int tile = g.tile_first + (int)blockIdx.y;
-  if (tile >= *g.n_tiles) return;
-  const int e = g.tiles[3 * tile];
-  const int row_lo = g.offsets[e] + g.tiles[3 * tile + 1];
-  const int nrows = g.tiles[3 * tile + 2];
+  const int slot = g.tile_first + (int)blockIdx.y;
+  if (slot >= *g.n_tiles) return;
+  // Chunks of one expert read the same weights.  Within the expert's blocks (dispatched in the
+  // order x + gridDim.x * y) the order is made [group of 8 N tiles][chunk][N tile in the group]:
+  // the blocks that share an N tile start together, 8 block ids apart (same XCD), so the weight
+  // lines one of them brings into that XCD's L2 are still there for the others.
+  const int first = g.tiles[TILE_REC * slot + 3], nsib = g.tiles[TILE_REC * slot + 4];
+  const int lg = (int)blockIdx.x + (int)gridDim.x * (slot - first);
+  const int rem = lg % (8 * nsib);
+  const int ntile = lg / (8 * nsib) * 8 + (rem & 7);
+  const int tile = first + (rem >> 3);
+  const int e = g.tiles[TILE_REC * tile];
+  const int row_lo = g.offsets[e] + g.tiles[TILE_REC * tile + 1];
+  const int nrows = g.tiles[TILE_REC * tile + 2];
   switch ((nrows + 31) >> 5) {      // 32-row tiles of the chunk
-    case 1: gemm_chunk<SILU, 1, 3>(g, smem, e, row_lo, nrows); break;
-    case 2: gemm_chunk<SILU, 2, 3>(g, smem, e, row_lo, nrows); break;
-    case 3: gemm_chunk<SILU, 3, 3>(g, smem, e, row_lo, nrows); break;
-    case 4: gemm_chunk<SILU, 4, 3>(g, smem, e, row_lo, nrows); break;
-    case 5: gemm_chunk<SILU, 5, 2>(g, smem, e, row_lo, nrows); break;
-    case 6: gemm_chunk<SILU, 6, 2>(g, smem, e, row_lo, nrows); break;
-    case 7: gemm_chunk<SILU, 7, 2>(g, smem, e, row_lo, nrows); break;
-    default: gemm_chunk<SILU, 8, 2>(g, smem, e, row_lo, nrows); break;
+    case 1: gemm_chunk<SILU, 1, 3>(g, smem, ntile, e, row_lo, nrows); break;
+    case 2: gemm_chunk<SILU, 2, 3>(g, smem, ntile, e, row_lo, nrows); break;
+    case 3: gemm_chunk<SILU, 3, 3>(g, smem, ntile, e, row_lo, nrows); break;
+    case 4: gemm_chunk<SILU, 4, 3>(g, smem, ntile, e, row_lo, nrows); break;
+    case 5: gemm_chunk<SILU, 5, 2>(g, smem, ntile, e, row_lo, nrows); break;
+    case 6: gemm_chunk<SILU, 6, 2>(g, smem, ntile, e, row_lo, nrows); break;
+    case 7: gemm_chunk<SILU, 7, 2>(g, smem, ntile, e, row_lo, nrows); break;
+    default: gemm_chunk<SILU, 8, 2>(g, smem, ntile, e, row_lo, nrows); break;
   }
 }
 
-// Y[t, :] = sum_i gate[t,i] * (sum_z Ybuf[z][inv[t*k+i], :]), rounded once to bf16.  One block
-// per token; fixed summation order (z inner, i outer).
+// Y[t, :] = sum_i gate[t,i] * (sum_z Ybuf[z][inv[t*k+i], :]), rounded once to bf16.  Block (t, j)
+// takes columns j*1024 .. j*1024+1023 of token t, four per thread; the partial sums of one slot are
+// fetched together (independent loads) and added in a fixed order (z inner, i outer).
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ ybuf,
                                                        const int32_t* __restrict__ inv,
                                                        const float* __restrict__ gate,
                                                        bf16_t* __restrict__ Y, int H, int k, int n_split,
                                                        size_t split_stride) {
   const int t = blockIdx.x;
-  for (int c = threadIdx.x * 4; c < H; c += blockDim.x * 4) {
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int i = 0; i < k; ++i) {
-      const int p = inv[t * k + i];
-      if (p < 0) continue;
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      for (int z = 0; z < n_split; ++z) {
-        const f32x4 w = *reinterpret_cast<const f32x4*>(ybuf + z * split_stride + (size_t)p * H + c);
-        v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
-      }
-      const float g = gate[t * k + i];
-      acc.x = fmaf(g, v.x, acc.x); acc.y = fmaf(g, v.y, acc.y);
-      acc.z = fmaf(g, v.z, acc.z); acc.w = fmaf(g, v.w, acc.w);
-    }
-    const uint32_t lo = (uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16);
-    const uint32_t hi = (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16);
-    *reinterpret_cast<uint2*>(Y + (size_t)t * H + c) = make_uint2(lo, hi);
+  const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
+  if (c >= H) return;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < k; ++i) {
+    const int p = inv[t * k + i];
+    if (p < 0) continue;
+    const float* src = ybuf + (size_t)p * H + c;
+    f32x4 w[MAX_KSPLIT];
+#pragma unroll
+    for (int z = 0; z < MAX_KSPLIT; ++z)
+      if (z < n_split) w[z] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src + z * split_stride));
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int z = 0; z < MAX_KSPLIT; ++z)
+      if (z < n_split) { v.x += w[z].x; v.y += w[z].y; v.z += w[z].z; v.w += w[z].w; }
+    const float g = gate[t * k + i];
+    acc.x = fmaf(g, v.x, acc.x); acc.y = fmaf(g, v.y, acc.y);
+    acc.z = fmaf(g, v.z, acc.z); acc.w = fmaf(g, v.w, acc.w);
   }
+  const uint32_t lo = (uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16);
+  const uint32_t hi = (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16);
+  *reinterpret_cast<uint2*>(Y + (size_t)t * H + c) = make_uint2(lo, hi);
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -353,7 +388,7 @@ Carve carve(const Shape& sh, int32_t T, void* base) {
   c.offsets = reinterpret_cast<int32_t*>(take((sh.E + 1) * sizeof(int32_t)));
   c.perm = reinterpret_cast<int32_t*>(take(n * sizeof(int32_t)));
   c.inv = reinterpret_cast<int32_t*>(take(n * sizeof(int32_t)));
-  c.tiles = reinterpret_cast<int32_t*>(take(3 * max_tiles * sizeof(int32_t)));
+  c.tiles = reinterpret_cast<int32_t*>(take(TILE_REC * max_tiles * sizeof(int32_t)));
   c.n_tiles = reinterpret_cast<int32_t*>(take(sizeof(int32_t)));
   c.hbuf = reinterpret_cast<bf16_t*>(take(n * sh.F * sizeof(bf16_t)));
   c.ybuf = reinterpret_cast<float*>(take((size_t)MAX_KSPLIT * n * sh.H * sizeof(float)));
@@ -371,9 +406,7 @@ size_t prefill_workspace_bytes(const Shape& sh, int32_t T) { return carve(sh, T,
 
 int prefill_chunks_of(int32_t count) {
   if (count <= 0) return 0;
-  const int nch = (count + BMX - 1) / BMX;
-  const int per = ((count + nch - 1) / nch + 31) & ~31;
-  return (count + per - 1) / per;
+  return (count + BMX - 1) / BMX;
 }
 
 namespace {
@@ -458,7 +491,7 @@ hipError_t prefill_combine(hipStream_t s, const Shape& sh, const float* gate, in
   const Carve c = carve(sh, T, workspace);
   int n_split, k_per_split;
   w2_split(sh, &n_split, &k_per_split);
-  combine_kernel<<<T, 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split,
+  combine_kernel<<<dim3(T, (sh.H + 1023) / 1024), 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split,
                                    (size_t)T * sh.k * sh.H);
   return hipGetLastError();
 }
