@@ -43,9 +43,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--tokens", type=int, default=None, help="tokens per step (default: the workload's 256)")
-    ap.add_argument("--cacheless-tokens", type=int, default=3,
+    ap.add_argument("--cacheless-tokens", type=int, default=10,
                     help="tokens of the 32-layer cacheless stack to time (0 = skip)")
-    ap.add_argument("--cpu-tokens", type=int, default=3, help="tokens the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-tokens", type=int, default=40, help="tokens the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--prefill-iters", type=int, default=5, help="timed prefill calls of 512 tokens (0 = skip)")
     ap.add_argument("--probe-mib", type=int, default=672,
                     help="size of the plain read/copy probe that measures the HBM and host-link ceilings (0 = skip)")
@@ -156,7 +156,7 @@ def main() -> int:
                     "ffn_down_GBps": round(down_bytes / (down_ms * 1e-3) / 1e9, 1)}
         log(f"[bench] kernels: up {up_ms * 1e3:.1f} us ({achieved:.0f} GB/s), down {down_ms * 1e3:.1f} us, "
             f"route {route_ms * 1e3:.1f} us")
-    Y_keep = harness.from_device(Y[:4]).copy()
+    Y_keep = harness.from_device(Y[:max(4, args.cpu_tokens)]).copy()
     stack.close()
 
     # ---- prefill: 512 tokens in one call, skewed routing, grouped GEMM on the matrix cores
@@ -226,15 +226,22 @@ def main() -> int:
         xs = [harness.to_device(r) for r in x_rows]
         yc = torch.empty_like(xs[0])
         s = B.odmoe_stats()
-        B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)        # warm-up token
+        for _ in range(2):                                               # warm-up tokens
+            B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)
         torch.cuda.synchronize()
         t_start = time.perf_counter()
         loads = 0
+        per_token = []
+        t_prev = t_start
         for t in range(n_tok):
             B.odmoe_decode_step(stc.handle, xs[t % len(xs)], yc, None, None, s)
             loads += s.loads
+            t_now = time.perf_counter()                                  # the step waits for every layer's ids
+            per_token.append((t_now - t_prev) * 1e3)
+            t_prev = t_now
         torch.cuda.synchronize()
         el = time.perf_counter() - t_start
+        pt = np.sort(np.asarray(per_token))
         idx_used = np.zeros((c.n_layers, c.top_k), np.int32)
         B.odmoe_decode_step(stc.handle, xs[0], yc, None, idx_used, s)
         t1 = time.perf_counter()
@@ -259,6 +266,9 @@ def main() -> int:
         h2d = loads * c.expert_bytes / el / 1e9
         out = {"workload": c.name, "tokens": n_tok, "unique_layers": len(layers_u),
                "tokens_per_s": round(n_tok / el, 4), "ms_per_token": round(step_ms, 3),
+               "ms_per_token_median_p10_p90": [round(float(np.median(pt)), 3),
+                                               round(float(pt[int(0.1 * (len(pt) - 1))]), 3),
+                                               round(float(pt[int(round(0.9 * (len(pt) - 1)))]), 3)],
                "h2d_GBps": round(h2d, 2), "h2d_frac_of_pcie5_x16": round(h2d / PCIE5_X16_GBPS, 4),
                "copy_only_ms_per_token": round(load_ms, 3), "kernel_ms_per_token": round(comp_ms, 3),
                "step_over_max_compute_load": round(step_ms / max(load_ms, comp_ms), 4),
