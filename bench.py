@@ -251,7 +251,8 @@ def main() -> int:
         el_hint = time.perf_counter() - t1
         s.t_step_ms = -1.0
         B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)        # one timed token for the breakdown
-        load_ms = s.t_load_ms
+        # the same bytes copied with no kernels in between (wall clock, all copy streams)
+        load_ms = B.odmoe_time_expert_loads(stc.handle, max(2, n_tok // 5))
         comp_ms = s.t_ffn_up_ms + s.t_ffn_down_ms + s.t_glue_ms
         step_ms = el / n_tok * 1e3
         # load-window check of the paper (Section 3.1): per layer, t^M = router + glue (the stand-in

@@ -27,7 +27,7 @@
  *   - hidden and ffn must be multiples of 8; 1 <= top_k <= min(n_experts, 8); n_experts <= 1024.
  *   - The caller owns every buffer it passes in; weight buffers must outlive the handle.
  *     Streams are borrowed (never destroyed here).  The library owns its slot pool, scratch
- *     buffers, events and, if none was given, its copy stream.
+ *     buffers, events and, if no copy stream was given, its copy streams.
  *   - Every call returns an odmoe_status.  Argument errors are detected before anything is
  *     enqueued.  HIP errors are reported as ODMOE_EHIP by the call that observes them.
  *     odmoe_last_error() gives a thread-local message for the last failing call.
@@ -76,7 +76,8 @@ typedef struct {
   /* kernel / copy times are HIP-event times summed over the layers of one call; they are 0
      unless timing was asked for (see odmoe_decode_step) */
   float t_route_ms;    /* router GEMV + top-k gate kernel */
-  float t_load_ms;     /* host->HBM expert copies (copy stream) */
+  float t_load_ms;     /* host->HBM expert copies: sum of the copies' own durations (copies on
+                          different copy streams may overlap, so this can exceed wall time) */
   float t_ffn_up_ms;   /* w1/w3 GEMV + SiLU gate kernel */
   float t_ffn_down_ms; /* w2 GEMV + weighted combine kernel */
   float t_glue_ms;     /* inter-layer glue kernel */
@@ -97,7 +98,9 @@ typedef struct {
  *               n_slots == 0: DEVICE pointers.  n_slots > 0: HOST pointers to PINNED memory
  *               (hipHostMalloc / torch pin_memory; odmoe_pinned_alloc provides it too).
  *   compute_stream  hipStream_t as void*; NULL = the null stream.
- *   copy_stream     hipStream_t for host->HBM copies; NULL = the library creates one.
+ *   copy_stream     hipStream_t for host->HBM copies; NULL = the library creates four and rotates
+ *                   the copies over them (back-to-back copies on one stream leave gaps that
+ *                   cost about 4 % of the link rate for 17 MB experts).
  *   out         receives the handle.
  * Allocates S*expert_bytes of HBM for the slot pool plus small scratch.  n_slots > 0 needs
  * n_slots >= top_k.  Returns EINVAL / ENOMEM / EHIP; on failure *out is NULL.
@@ -106,7 +109,7 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w,
                      const void* const* router_b, const void* const* expert_w,
                      void* compute_stream, void* copy_stream, odmoe_layer_t** out);
 
-/* Waits for both streams, frees everything the library owns.  NULL is allowed. */
+/* Waits for the compute and copy streams, frees everything the library owns.  NULL is allowed. */
 int odmoe_layer_destroy(odmoe_layer_t* h);
 
 /*
@@ -119,8 +122,8 @@ int odmoe_route_topk(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t
 
 /*
  * On-demand expert loading EL_l (Sections 1, 3.1): enqueue the copy of expert (layer, expert)
- * from pinned host memory into a free HBM slot on the copy stream.  The copy waits (stream
- * side) for the kernels that last read that slot.  If the expert is already loading or
+ * from pinned host memory into a free HBM slot on a copy stream.  The copy waits (stream
+ * side) for the kernels that last read that slot and for an earlier copy into it.  If the expert is already loading or
  * ready, its slot is returned and nothing is copied.  *slot_out (may be NULL) gets the slot.
  * EBUSY when every slot is occupied; EINVAL in resident mode or for a bad index.
  */
@@ -199,6 +202,16 @@ int odmoe_probe_hbm(void* dst_dev, const void* src_dev, uint64_t bytes, int32_t 
  */
 int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t n_tokens,
                               int32_t reps, float* route_us, float* ffn_up_us, float* ffn_down_us);
+
+/*
+ * Measurement aid: the host->HBM copies of `n_tokens` decode tokens (n_layers * top_k expert
+ * copies each, layer l taking experts (l*top_k + i) mod n_experts) issued exactly as
+ * odmoe_decode_step issues them (same copy streams, slots taken round-robin) but with no kernels
+ * in between: *ms_per_token gets the wall-clock time per token.  This is the "load" leg of
+ * max(compute, load) a cacheless step is compared with.  Cacheless mode only; ESTATE while an
+ * expert holds a slot.  Blocks.
+ */
+int odmoe_time_expert_loads(odmoe_layer_t* h, int32_t n_tokens, float* ms_per_token);
 
 /*
  * Longest expert-loading time that causes no compute stall (Section 3.1, load-window

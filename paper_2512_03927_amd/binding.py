@@ -23,7 +23,7 @@ EXPORTS = (
     "odmoe_layer_init", "odmoe_layer_destroy", "odmoe_route_topk", "odmoe_expert_load_async",
     "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_decode_step", "odmoe_pinned_alloc",
     "odmoe_pinned_free", "odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_probe_hbm",
-    "odmoe_time_decode_kernels", "odmoe_load_window_ms", "odmoe_slot_groups",
+    "odmoe_time_decode_kernels", "odmoe_time_expert_loads", "odmoe_load_window_ms", "odmoe_slot_groups",
 )
 
 
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
     L.odmoe_probe_hbm.argtypes = [vp, vp, u64, i32, vp]
     L.odmoe_time_decode_kernels.argtypes = [vp, i32, vp, i32, i32, C.POINTER(C.c_float), C.POINTER(C.c_float),
                                             C.POINTER(C.c_float)]
+    L.odmoe_time_expert_loads.argtypes = [vp, i32, C.POINTER(C.c_float)]
     L.odmoe_load_window_ms.argtypes = [i32, C.c_double, C.c_double]
     L.odmoe_load_window_ms.restype = C.c_double
     L.odmoe_slot_groups.argtypes = [vp]
@@ -185,6 +186,13 @@ def odmoe_time_decode_kernels(h: int, layer: int, x_dev, n_tokens: int, reps: in
     _check(lib().odmoe_time_decode_kernels(h, layer, _ptr(x_dev), n_tokens, reps, C.byref(r), C.byref(u),
                                            C.byref(d)))
     return r.value, u.value, d.value
+
+
+def odmoe_time_expert_loads(h: int, n_tokens: int) -> float:
+    """Wall-clock ms per token of the expert copies of n_tokens decode tokens, no kernels."""
+    ms = C.c_float()
+    _check(lib().odmoe_time_expert_loads(h, n_tokens, C.byref(ms)))
+    return ms.value
 
 
 def odmoe_load_window_ms(n_groups: int, t_main_ms: float, t_worker_ms: float) -> float:

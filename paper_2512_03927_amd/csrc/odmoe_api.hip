@@ -59,6 +59,11 @@ struct odmoe_layer {
   DecodeScheduler* sched = nullptr;
   std::vector<hipEvent_t> ready_ev, done_ev;  // per slot
   std::vector<char> done_pending;             // done_ev[slot] recorded since the slot's last copy
+  std::vector<char> copied_once;              // ready_ev[slot] has been recorded at least once
+  // Copies rotate over these streams (copy and, when the library owns it, three more): back-to-back
+  // copies on one stream leave a gap of about 10 us between them, which matters for small experts.
+  std::vector<hipStream_t> copy_ring;
+  uint32_t next_copy = 0;
 
   // scratch
   float* hbuf = nullptr;      // [k*F] fp32
@@ -119,7 +124,8 @@ void free_all(odmoe_layer* h) {
   if (h->eptr_dev) (void)hipFree((void*)h->eptr_dev);
   if (h->idx_pin) (void)hipHostFree(h->idx_pin);
   if (h->prefill_ws) (void)hipFree(h->prefill_ws);
-  if (h->own_copy && h->copy) (void)hipStreamDestroy(h->copy);
+  if (h->own_copy)
+    for (hipStream_t cs : h->copy_ring) if (cs) (void)hipStreamDestroy(cs);
   delete h->sched;
   delete h->pool;
   delete h;
@@ -135,16 +141,20 @@ int check_layer(const odmoe_layer* h, int32_t layer) {
 // Enqueue the copy of (layer, expert) into `slot` on the copy stream.
 int enqueue_load(odmoe_layer* h, int32_t layer, int32_t expert, int32_t slot, hipEvent_t t0 = nullptr,
                  hipEvent_t t1 = nullptr) {
+  hipStream_t cs = h->copy_ring[h->next_copy++ % h->copy_ring.size()];
   if (h->done_pending[slot]) {
-    HIP_TRY(hipStreamWaitEvent(h->copy, h->done_ev[slot], 0));
+    HIP_TRY(hipStreamWaitEvent(cs, h->done_ev[slot], 0));
     h->done_pending[slot] = 0;
   }
+  // An earlier copy into this slot (possibly on another stream, possibly never read) comes first.
+  if (h->copied_once[slot] && h->copy_ring.size() > 1) HIP_TRY(hipStreamWaitEvent(cs, h->ready_ev[slot], 0));
   const void* src = h->expert_w[(size_t)layer * h->cfg.n_experts + expert];
-  if (t0) HIP_TRY(hipEventRecord(t0, h->copy));
+  if (t0) HIP_TRY(hipEventRecord(t0, cs));
   HIP_TRY(hipMemcpyAsync(h->pool_mem + (size_t)slot * h->expert_bytes, src, h->expert_bytes,
-                         hipMemcpyHostToDevice, h->copy));
-  if (t1) HIP_TRY(hipEventRecord(t1, h->copy));
-  HIP_TRY(hipEventRecord(h->ready_ev[slot], h->copy));
+                         hipMemcpyHostToDevice, cs));
+  if (t1) HIP_TRY(hipEventRecord(t1, cs));
+  HIP_TRY(hipEventRecord(h->ready_ev[slot], cs));
+  h->copied_once[slot] = 1;
   return ODMOE_OK;
 }
 
@@ -276,6 +286,29 @@ int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev
   return ODMOE_OK;
 }
 
+int odmoe_time_expert_loads(odmoe_layer_t* h, int32_t n_tokens, float* ms_per_token) {
+  if (!h || !ms_per_token) return fail(ODMOE_EINVAL, "NULL argument");
+  if (!h->pool) return fail(ODMOE_EINVAL, "resident mode has no expert loads");
+  if (n_tokens <= 0) return fail(ODMOE_EINVAL, "n_tokens = %d", n_tokens);
+  const int S = h->cfg.n_slots, L = h->cfg.n_layers, k = h->cfg.top_k, E = h->cfg.n_experts;
+  if (h->pool->n_free() != S) return fail(ODMOE_ESTATE, "an expert holds a slot");
+  HIP_TRY(hipStreamSynchronize(h->compute));
+  for (hipStream_t cs : h->copy_ring) HIP_TRY(hipStreamSynchronize(cs));
+  const auto t0 = std::chrono::steady_clock::now();
+  int slot = 0;
+  for (int t = 0; t < n_tokens; ++t)
+    for (int l = 0; l < L; ++l)
+      for (int i = 0; i < k; ++i) {
+        const int rc = enqueue_load(h, l, (l * k + i) % E, slot);
+        if (rc) return rc;
+        slot = slot + 1 == S ? 0 : slot + 1;
+      }
+  for (hipStream_t cs : h->copy_ring) HIP_TRY(hipStreamSynchronize(cs));
+  *ms_per_token =
+      std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - t0).count() / n_tokens;
+  return ODMOE_OK;
+}
+
 double odmoe_load_window_ms(int32_t n_groups, double t_main_ms, double t_worker_ms) {
   if (n_groups < 1) return 0.0;
   return n_groups * t_main_ms + (n_groups - 1) * t_worker_ms;
@@ -355,11 +388,18 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
       INIT_TRY(hipEventCreateWithFlags(&h->ready_ev[s], hipEventDisableTiming), ODMOE_EHIP);
       INIT_TRY(hipEventCreateWithFlags(&h->done_ev[s], hipEventDisableTiming), ODMOE_EHIP);
     }
+    h->copied_once.assign(S, 0);
     if (copy_stream) {
       h->copy = static_cast<hipStream_t>(copy_stream);
+      h->copy_ring.push_back(h->copy);
     } else {
-      INIT_TRY(hipStreamCreateWithFlags(&h->copy, hipStreamNonBlocking), ODMOE_EHIP);
       h->own_copy = true;
+      for (int i = 0; i < 4; ++i) {
+        hipStream_t cs = nullptr;
+        INIT_TRY(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking), ODMOE_EHIP);
+        h->copy_ring.push_back(cs);
+      }
+      h->copy = h->copy_ring[0];
     }
   }
 #undef INIT_TRY
@@ -370,7 +410,11 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
 int odmoe_layer_destroy(odmoe_layer_t* h) {
   if (!h) return ODMOE_OK;
   hipError_t e1 = hipStreamSynchronize(h->compute);
-  hipError_t e2 = h->copy ? hipStreamSynchronize(h->copy) : hipSuccess;
+  hipError_t e2 = hipSuccess;
+  for (hipStream_t cs : h->copy_ring) {
+    const hipError_t ec = hipStreamSynchronize(cs);
+    if (ec != hipSuccess) e2 = ec;
+  }
   free_all(h);
   if (e1 != hipSuccess) return fail(ODMOE_EHIP, "compute stream: %s", hipGetErrorString(e1));
   if (e2 != hipSuccess) return fail(ODMOE_EHIP, "copy stream: %s", hipGetErrorString(e2));
@@ -629,7 +673,7 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
   if (stats) {
     stats->t_route_ms = stats->t_load_ms = stats->t_ffn_up_ms = stats->t_ffn_down_ms = stats->t_glue_ms = 0.f;
     if (timed) {
-      if (h->copy) HIP_TRY(hipStreamSynchronize(h->copy));
+      for (hipStream_t cs : h->copy_ring) HIP_TRY(hipStreamSynchronize(cs));
       for (int l = 0; l < L; ++l) {
         float ms = 0.f;
         // route includes, in cacheless mode, the wait for this layer's expert copies

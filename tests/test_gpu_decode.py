@@ -220,6 +220,16 @@ def test_hints_change_timing_only(H):
             assert np.array_equal(H.from_device(y4), base)
             assert s4.t_step_ms > 0 and s4.t_ffn_up_ms > 0 and s4.t_ffn_down_ms > 0 and s4.t_load_ms > 0
             assert s4.t_route_ms > 0 and s4.t_glue_ms > 0
+        # the copy-only replay moves the same bytes, leaves every slot free, and the stack still
+        # gives the same output afterwards (the slots it overwrote held no expert)
+        from paper_2512_03927_amd import binding as B
+        ms = B.odmoe_time_expert_loads(st.handle, 2)
+        assert ms > 0
+        y5, idx5, s5 = st.decode(x)
+        assert np.array_equal(H.from_device(y5), base) and s5.loads == L * k
+    with H.MoEStack(cfg.small(n_slots=0), layers) as st_res:
+        with pytest.raises(RuntimeError):
+            B.odmoe_time_expert_loads(st_res.handle, 1)          # resident mode has no loads
 
 
 def test_hint_recall_is_what_was_planted(H):

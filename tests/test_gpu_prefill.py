@@ -76,9 +76,10 @@ def test_prefill_unsupported_shape_falls_back_to_per_token_path(H):
 
 
 def test_prefill_all_tokens_to_one_expert_and_repeat_calls(H):
-    """Degenerate routing: one expert gets every token (4 M-tiles), the others none; the call is
-    repeatable (workspace reuse) and a smaller batch after a larger one is still right."""
-    cfg = synth.MoEConfig("t", 128, 256, 4, 1, dtype="bf16", n_tokens=500, seed=24)
+    """Degenerate routing: one expert gets every token (4 chunks of 225 rows that share every
+    weight tile), the others none; the call is repeatable (workspace reuse) and a smaller batch
+    after a larger one is still right."""
+    cfg = synth.MoEConfig("t", 128, 256, 4, 1, dtype="bf16", n_tokens=900, seed=24)
     Wg, _, experts = synth.layer_weights(cfg)
     b = np.array([0.0, 50.0, 0.0, 0.0], np.float32)          # expert 1 always wins
     X = synth.tokens(cfg)
