@@ -164,59 +164,52 @@ __device__ __forceinline__ void stage_vec(const T* __restrict__ src, float* __re
 }
 
 // ---------------------------------------------------------------------------------------------
-// Router GEMV + top-k + renormalised softmax gate.  One block per token.
+// Router GEMV + top-k + renormalised softmax gate.
 // Logits are summed in float64 and rounded once to fp32, so the selection agrees with a float64
 // reference rounded the same way regardless of summation order.  Ties: lowest index first.
 // ---------------------------------------------------------------------------------------------
+
+// One wave: logit of one expert row against one token, float64 accumulation (all lanes get it).
 template <typename T>
-__global__ __launch_bounds__(512) void route_topk_kernel(const T* __restrict__ Wg,
-                                                          const float* __restrict__ bias,
-                                                          const T* __restrict__ x, int H, int E, int k,
-                                                          int32_t* __restrict__ idx,
-                                                          float* __restrict__ gate,
-                                                          int32_t* __restrict__ idx_mirror,
-                                                          const void* const* __restrict__ table,
-                                                          int table_off,
-                                                          const void** __restrict__ eptr_out) {
+__device__ __forceinline__ double wave_logit(const T* __restrict__ row, const T* __restrict__ xt, int nvec,
+                                             int lane) {
   constexpr int VEC = DT<T>::VEC;
-  __shared__ float slog[ODMOE_MAX_EXPERTS];
-  __shared__ float sel_v[ODMOE_MAX_TOPK];
-  __shared__ int sel_i[ODMOE_MAX_TOPK];
-  const int t = blockIdx.x;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  const T* xt = x + (size_t)t * H;
-  const int nvec = H / VEC;
+  double acc0 = 0.0, acc1 = 0.0;  // two chains: half the dependent-FMA latency
+  int v = lane;
+  for (; v + WAVE < nvec; v += 2 * WAVE) {
+    float fw[VEC], fx[VEC], gw[VEC], gx[VEC];
+    DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
+    DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
+    DT<T>::unpack(load16(row + (size_t)(v + WAVE) * VEC), gw);
+    DT<T>::unpack(load16(xt + (size_t)(v + WAVE) * VEC), gx);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) {
+      acc0 = fma((double)fw[j], (double)fx[j], acc0);
+      acc1 = fma((double)gw[j], (double)gx[j], acc1);
+    }
+  }
+  for (; v < nvec; v += WAVE) {
+    float fw[VEC], fx[VEC];
+    DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
+    DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc0 = fma((double)fw[j], (double)fx[j], acc0);
+  }
+  return wave_sum(acc0 + acc1);
+}
+
+// The whole block: from the E logits in slog (LDS, complete and visible) to idx / gate of token t.
+// sel_v / sel_i: LDS scratch of ODMOE_MAX_TOPK entries.
+__device__ __forceinline__ void select_topk_and_gate(const float* slog, float* sel_v, int* sel_i, int E,
+                                                     int k, int t, int32_t* __restrict__ idx,
+                                                     float* __restrict__ gate,
+                                                     int32_t* __restrict__ idx_mirror,
+                                                     const void* const* __restrict__ table,
+                                                     int table_off, const void** __restrict__ eptr_out) {
   // NaN logits take no position in the order below; pre-filling the selection keeps every
   // index in range even then (which experts are picked is unspecified in that case).
   if (threadIdx.x < k) { sel_v[threadIdx.x] = 0.f; sel_i[threadIdx.x] = threadIdx.x; }
-  for (int e = wave; e < E; e += nw) {
-    const T* row = Wg + (size_t)e * H;
-    double acc0 = 0.0, acc1 = 0.0;  // two chains: half the dependent-FMA latency
-    int v = lane;
-    for (; v + WAVE < nvec; v += 2 * WAVE) {
-      float fw[VEC], fx[VEC], gw[VEC], gx[VEC];
-      DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
-      DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
-      DT<T>::unpack(load16(row + (size_t)(v + WAVE) * VEC), gw);
-      DT<T>::unpack(load16(xt + (size_t)(v + WAVE) * VEC), gx);
-#pragma unroll
-      for (int j = 0; j < VEC; ++j) {
-        acc0 = fma((double)fw[j], (double)fx[j], acc0);
-        acc1 = fma((double)gw[j], (double)gx[j], acc1);
-      }
-    }
-    for (; v < nvec; v += WAVE) {
-      float fw[VEC], fx[VEC];
-      DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
-      DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
-#pragma unroll
-      for (int j = 0; j < VEC; ++j) acc0 = fma((double)fw[j], (double)fx[j], acc0);
-    }
-    const double acc = wave_sum(acc0 + acc1);
-    if (lane == 0) slog[e] = (float)(acc + (bias ? (double)bias[e] : 0.0));
-  }
   __syncthreads();
-
   // Position of every expert in the total order (logit descending, index ascending): the
   // number of experts that come before it.  Experts at positions < k are the selection.
   for (int e = threadIdx.x; e < E; e += blockDim.x) {
@@ -240,6 +233,69 @@ __global__ __launch_bounds__(512) void route_topk_kernel(const T* __restrict__ W
     if (idx_mirror) idx_mirror[(size_t)t * k + i] = e;
     if (eptr_out) eptr_out[(size_t)t * k + i] = table[table_off + e];
   }
+}
+
+// One block per token: one wave per expert, in rounds.
+template <typename T>
+__global__ __launch_bounds__(512) void route_topk_kernel(const T* __restrict__ Wg,
+                                                          const float* __restrict__ bias,
+                                                          const T* __restrict__ x, int H, int E, int k,
+                                                          int32_t* __restrict__ idx,
+                                                          float* __restrict__ gate,
+                                                          int32_t* __restrict__ idx_mirror,
+                                                          const void* const* __restrict__ table,
+                                                          int table_off,
+                                                          const void** __restrict__ eptr_out) {
+  __shared__ float slog[ODMOE_MAX_EXPERTS];
+  __shared__ float sel_v[ODMOE_MAX_TOPK];
+  __shared__ int sel_i[ODMOE_MAX_TOPK];
+  const int t = blockIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const T* xt = x + (size_t)t * H;
+  const int nvec = H / DT<T>::VEC;
+  for (int e = wave; e < E; e += nw) {
+    const double acc = wave_logit<T>(Wg + (size_t)e * H, xt, nvec, lane);
+    if (lane == 0) slog[e] = (float)(acc + (bias ? (double)bias[e] : 0.0));
+  }
+  __syncthreads();
+  select_topk_and_gate(slog, sel_v, sel_i, E, k, t, idx, gate, idx_mirror, table, table_off, eptr_out);
+}
+
+// Few tokens, many experts: gridDim.x blocks per token, each taking 8 experts (one per wave), so
+// the router matrix is read by many CUs at once.  The logits go to `logits` [T, E]; the block
+// that finishes last for its token (a ticket from counters[t], which it leaves at zero again)
+// does the selection.  No block waits for another.
+template <typename T>
+__global__ __launch_bounds__(512) void route_topk_split_kernel(
+    const T* __restrict__ Wg, const float* __restrict__ bias, const T* __restrict__ x, int H, int E, int k,
+    int32_t* __restrict__ idx, float* __restrict__ gate, int32_t* __restrict__ idx_mirror,
+    const void* const* __restrict__ table, int table_off, const void** __restrict__ eptr_out,
+    float* logits, int32_t* counters) {
+  __shared__ float slog[ODMOE_MAX_EXPERTS];
+  __shared__ float sel_v[ODMOE_MAX_TOPK];
+  __shared__ int sel_i[ODMOE_MAX_TOPK];
+  __shared__ int s_ticket;
+  const int t = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int e = blockIdx.x * 8 + wave;
+  if (e < E) {
+    const double acc = wave_logit<T>(Wg + (size_t)e * H, x + (size_t)t * H, H / DT<T>::VEC, lane);
+    if (lane == 0)
+      __hip_atomic_store(logits + (size_t)t * E + e, (float)(acc + (bias ? (double)bias[e] : 0.0)),
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __threadfence();       // this block's logits are visible device-wide before its ticket is
+  __syncthreads();
+  if (threadIdx.x == 0)
+    s_ticket = __hip_atomic_fetch_add(counters + t, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_ticket != (int)gridDim.x - 1) return;
+  __threadfence();
+  for (int j = threadIdx.x; j < E; j += blockDim.x)
+    slog[j] = __hip_atomic_load(logits + (size_t)t * E + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) counters[t] = 0;
+  __syncthreads();
+  select_topk_and_gate(slog, sel_v, sel_i, E, k, t, idx, gate, idx_mirror, table, table_off, eptr_out);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -535,10 +591,21 @@ hipError_t kernels_init() {
 hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
                              const void* x, int32_t T, int32_t* idx, float* gate,
                              int32_t* idx_mirror, const void* const* table, int32_t table_off,
-                             const void** eptr_out) {
+                             const void** eptr_out, const RouteScratch* scratch) {
   if (T <= 0) return hipSuccess;
-  // one wave per expert up to 8 waves; NaN logits never enter the selection (k entries may then
-  // stay unwritten: documented as unspecified)
+  if (scratch && scratch->logits && sh.E > 8 && T <= scratch->max_tokens) {
+    const dim3 grid((sh.E + 7) / 8, T);
+    if (sh.dtype == ODMOE_F32)
+      route_topk_split_kernel<float><<<grid, 512, 0, s>>>(
+          static_cast<const float*>(Wg), b, static_cast<const float*>(x), sh.H, sh.E, sh.k, idx, gate,
+          idx_mirror, table, table_off, eptr_out, scratch->logits, scratch->counters);
+    else
+      route_topk_split_kernel<bf16_t><<<grid, 512, 0, s>>>(
+          static_cast<const bf16_t*>(Wg), b, static_cast<const bf16_t*>(x), sh.H, sh.E, sh.k, idx, gate,
+          idx_mirror, table, table_off, eptr_out, scratch->logits, scratch->counters);
+    return hipGetLastError();
+  }
+  // one wave per expert up to 8 waves
   const int threads = sh.E >= 8 ? 512 : (sh.E >= 4 ? 256 : 128);
   if (sh.dtype == ODMOE_F32)
     route_topk_kernel<float><<<T, threads, 0, s>>>(static_cast<const float*>(Wg), b,

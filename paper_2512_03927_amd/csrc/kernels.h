@@ -24,14 +24,25 @@ struct Shape {
   int32_t dtype;  // odmoe_dtype
 };
 
+// Device scratch that lets the router spread one token over several blocks: logits
+// [max_tokens, E] fp32 and counters [max_tokens] int32, the counters zero before the first launch
+// (every launch leaves them zero).  Launches that share a scratch must not overlap.
+struct RouteScratch {
+  float* logits;
+  int32_t* counters;
+  int32_t max_tokens;
+};
+constexpr int32_t ROUTE_SPLIT_MAX_TOKENS = 16;
+
 // Router GEMV + top-k + gate for T tokens.  idx_mirror (may be null) is a second int32[T*k]
 // destination (host-mapped pinned memory) written together with idx.  With eptr_out != null the
 // kernel also stores table[table_off + idx] there (T*k pointers), which saves the FFN kernels
-// one dependent load.
+// one dependent load.  With a scratch, more than 8 experts and T <= scratch->max_tokens the
+// experts of a token are spread over several blocks (same results).
 hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
                              const void* x, int32_t T, int32_t* idx, float* gate,
                              int32_t* idx_mirror, const void* const* table, int32_t table_off,
-                             const void** eptr_out);
+                             const void** eptr_out, const RouteScratch* scratch = nullptr);
 
 // h[i, :] = silu(W1 x) * (W3 x) for the k selected experts of ONE token.  hbuf: fp32 [k, F].
 hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,

@@ -75,6 +75,7 @@ struct odmoe_layer {
   int32_t* idx_pin_dev = nullptr;
   const void** eptr_dev = nullptr;  // resident: [L*k] expert pointers resolved by the router kernel
   hipEvent_t route_ev = nullptr;
+  RouteScratch route_scratch{nullptr, nullptr, 0};  // lets few-token router launches use many CUs
   void* prefill_ws = nullptr;
   size_t prefill_ws_bytes = 0;
 
@@ -122,6 +123,8 @@ void free_all(odmoe_layer* h) {
   if (h->idx_dev) (void)hipFree(h->idx_dev);
   if (h->gate_dev) (void)hipFree(h->gate_dev);
   if (h->eptr_dev) (void)hipFree((void*)h->eptr_dev);
+  if (h->route_scratch.logits) (void)hipFree(h->route_scratch.logits);
+  if (h->route_scratch.counters) (void)hipFree(h->route_scratch.counters);
   if (h->idx_pin) (void)hipHostFree(h->idx_pin);
   if (h->prefill_ws) (void)hipFree(h->prefill_ws);
   if (h->own_copy)
@@ -257,13 +260,13 @@ int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev
   const float* bias = static_cast<const float*>(h->router_b[layer]);
   // warm-up + the routing every later launch uses
   T_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer], bias, x_dev, n_tokens, idx, gate, nullptr,
-                          nullptr, 0, nullptr));
+                          nullptr, 0, nullptr, &h->route_scratch));
   T_TRY(hipEventRecord(ev[0], h->compute));
   for (int r = 0; r < reps; ++r)
     for (int t = 0; t < n_tokens; ++t)
       T_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer], bias,
                               static_cast<const char*>(x_dev) + t * row, 1, idx + (size_t)t * k,
-                              gate + (size_t)t * k, nullptr, nullptr, 0, nullptr));
+                              gate + (size_t)t * k, nullptr, nullptr, 0, nullptr, &h->route_scratch));
   T_TRY(hipEventRecord(ev[1], h->compute));
   for (int r = 0; r < reps; ++r)
     for (int t = 0; t < n_tokens; ++t)
@@ -365,6 +368,14 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
   INIT_TRY(hipMalloc(&h->xbuf[1], H * h->esize), ODMOE_ENOMEM);
   INIT_TRY(hipMalloc(&h->ybuf, H * h->esize), ODMOE_ENOMEM);
   INIT_TRY(hipMalloc(&h->idx_dev, (size_t)L * k * sizeof(int32_t)), ODMOE_ENOMEM);
+  if (h->cfg.n_experts > 8) {
+    INIT_TRY(hipMalloc(&h->route_scratch.logits,
+                       (size_t)ROUTE_SPLIT_MAX_TOKENS * h->cfg.n_experts * sizeof(float)), ODMOE_ENOMEM);
+    INIT_TRY(hipMalloc(&h->route_scratch.counters, ROUTE_SPLIT_MAX_TOKENS * sizeof(int32_t)), ODMOE_ENOMEM);
+    INIT_TRY(hipMemset(h->route_scratch.counters, 0, ROUTE_SPLIT_MAX_TOKENS * sizeof(int32_t)), ODMOE_EHIP);
+    INIT_TRY(hipDeviceSynchronize(), ODMOE_EHIP);  // the fill is done before any stream uses the counters
+    h->route_scratch.max_tokens = ROUTE_SPLIT_MAX_TOKENS;
+  }
   INIT_TRY(hipMalloc(&h->gate_dev, (size_t)L * k * sizeof(float)), ODMOE_ENOMEM);
   INIT_TRY(hipHostMalloc((void**)&h->idx_pin, (size_t)L * k * sizeof(int32_t), hipHostMallocMapped | hipHostMallocCoherent),
            ODMOE_ENOMEM);
@@ -430,7 +441,7 @@ int odmoe_route_topk(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t
   if (!x_dev || !idx_dev || !gate_dev) return fail(ODMOE_EINVAL, "x/idx/gate is NULL");
   HIP_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer],
                             static_cast<const float*>(h->router_b[layer]), x_dev, n_tokens, idx_dev,
-                            gate_dev, nullptr, nullptr, 0, nullptr));
+                            gate_dev, nullptr, nullptr, 0, nullptr, &h->route_scratch));
   return ODMOE_OK;
 }
 
@@ -619,7 +630,7 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
     if (timed) HIP_TRY(hipEventRecord(TE(l, 0), h->compute));
     HIP_TRY(launch_route_topk(h->compute, h->sh, h->router_w[l], static_cast<const float*>(h->router_b[l]),
                               cur, 1, idx_l, gate_l, h->idx_pin_dev + (size_t)l * k, h->table_dev, l * E,
-                              h->sched ? nullptr : h->eptr_dev + (size_t)l * k));
+                              h->sched ? nullptr : h->eptr_dev + (size_t)l * k, &h->route_scratch));
 
     ExpertSrc src{};
     int32_t slots[ODMOE_MAX_TOPK];

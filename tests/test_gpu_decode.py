@@ -113,8 +113,15 @@ def test_routing_ties_zero_router_and_bias(H):
     b[4] = -0.0
     for bias in (None, b):
         with H.MoEStack(cfg, [(Wg, bias, experts)]) as st:
-            idx, gate = st.route(0, H.to_device(X))
+            xd = H.to_device(X)
+            idx, gate = st.route(0, xd)
             idx, gate = idx.cpu().numpy(), gate.cpu().numpy()
+            # few tokens at a time go through the router variant that spreads a token's experts
+            # over several blocks: same bits, also when called repeatedly
+            for lo, hi in ((0, 16), (16, 19), (19, 20), (0, 16)):
+                i2, g2 = st.route(0, xd[lo:hi].contiguous())
+                assert np.array_equal(i2.cpu().numpy(), idx[lo:hi])
+                assert np.array_equal(g2.cpu().numpy(), gate[lo:hi])
         hit = 0
         for t in range(cfg.n_tokens):
             ri, rg, _ = O.route(Wg, bias, X[t], cfg.top_k)
@@ -128,9 +135,10 @@ def test_routing_ties_zero_router_and_bias(H):
     # all-zero router: idx = 0..k-1, g = 1/k exactly
     Z = np.zeros_like(Wg)
     with H.MoEStack(cfg, [(Z, None, experts)]) as st:
-        idx, gate = st.route(0, H.to_device(X))
-        assert (idx.cpu().numpy() == np.arange(cfg.top_k)).all()
-        assert (gate.cpu().numpy() == np.float32(1.0 / cfg.top_k)).all()
+        for n in (cfg.n_tokens, 3):
+            idx, gate = st.route(0, H.to_device(X[:n]))
+            assert (idx.cpu().numpy() == np.arange(cfg.top_k)).all()
+            assert (gate.cpu().numpy() == np.float32(1.0 / cfg.top_k)).all()
         # x = 0 -> y = 0 exactly
         x0 = st.empty_x(1).zero_()
         i0, g0 = st.route(0, x0)
