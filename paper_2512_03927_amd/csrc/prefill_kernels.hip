@@ -119,7 +119,7 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //   - the 128-column-wide block tile also halves the activation traffic per weight byte.
 //   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+127; out = bf16( silu(A W1^T) * (A W3^T) )
 //   !SILU : halves = weight rows n0..n0+127 / n0+128..n0+255; out = fp32 partial sums for K range
-//           blockIdx.z, [gridDim.z][rows, ldo]
+//           ksplit, [gridDim.z][rows, ldo]
 // grid: x = N tile, y = entry of the chunk list, z = K split.  K is a multiple of 64.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_slot(int row, int piece) { return row * BK + ((piece ^ (row & 7)) << 3); }
@@ -150,7 +150,7 @@ struct GemmArgs {
 };
 
 template <bool SILU, int NT, int NSTAGE>
-__device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int ntile, int e, int row_lo, int nrows) {
+__device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int ntile, int ksplit, int e, int row_lo, int nrows) {
   constexpr int A_INSTR = (NT + 1) / 2;                 // A fills per wave per K-step (64 rows each)
   constexpr int A_ROWS = 64 * A_INSTR;                  // rows of activations staged (NT 32-row tiles used)
   constexpr int MTW = (NT + 1) / 2;                     // 32-row tiles per wave: tiles wm, wm+2, wm+4, ...
@@ -167,7 +167,7 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
   const int K = g.K;
-  const int k_begin = blockIdx.z * g.k_per_split;
+  const int k_begin = ksplit * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split < K) ? k_begin + g.k_per_split : K;
   if (k_begin >= k_end) return;
   const int nk = (k_end - k_begin) / BK;
@@ -198,7 +198,7 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   // Blocks that run side by side start their K loops at different steps: rows of a row-major
   // matrix lie a multiple of 4 KB apart, so blocks marching through K in lockstep would keep
   // hitting the same memory channels.
-  const int kt0 = (int)(((unsigned)ntile * K_ROTATE + blockIdx.z * 7u) % (unsigned)nk);
+  const int kt0 = (int)(((unsigned)ntile * K_ROTATE + (unsigned)ksplit * 7u) % (unsigned)nk);
   auto step_offset = [&](int kt) {
     int kr = kt + kt0;
     kr = kr >= nk ? kr - nk : kr;
@@ -298,7 +298,7 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
           for (int b = 0; b < 2; ++b) {
             const int col = n0 + b * 128 + wn * 32 + fr;
             if (col < g.N)
-              ((__attribute__((address_space(1))) float*)g.out)[blockIdx.z * g.split_stride + p * g.ldo + col] =
+              ((__attribute__((address_space(1))) float*)g.out)[ksplit * g.split_stride + p * g.ldo + col] =
                   acc[mt][b][i];
           }
         }
@@ -310,14 +310,21 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
 template <bool SILU>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
-  const int slot = g.tile_first + (int)blockIdx.y;
+  // Blocks are dispatched in the order x + gridDim.x * (y + gridDim.y * z), round-robin over the
+  // 8 XCDs.  That order is re-read as [y][x][K split]: with 8 K splits every XCD works on one K
+  // range, so the blocks that read the same activation columns (all N tiles of a chunk) and the
+  // same weight tile (the chunks of an expert) share one L2.
+  const unsigned lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+  const int ksplit = (int)(lin % gridDim.z);
+  const int bx = (int)((lin / gridDim.z) % gridDim.x), by = (int)(lin / gridDim.z / gridDim.x);
+  const int slot = g.tile_first + by;
   if (slot >= *g.n_tiles) return;
   // Chunks of one expert read the same weights.  Within the expert's blocks (dispatched in the
   // order x + gridDim.x * y) the order is made [group of 8 N tiles][chunk][N tile in the group]:
   // the blocks that share an N tile start together, 8 block ids apart (same XCD), so the weight
   // lines one of them brings into that XCD's L2 are still there for the others.
   const int first = g.tiles[TILE_REC * slot + 3], nsib = g.tiles[TILE_REC * slot + 4];
-  const int lg = (int)blockIdx.x + (int)gridDim.x * (slot - first);
+  const int lg = bx + (int)gridDim.x * (slot - first);
   const int rem = lg % (8 * nsib);
   const int ntile = lg / (8 * nsib) * 8 + (rem & 7);
   const int tile = first + (rem >> 3);
@@ -325,14 +332,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) 
   const int row_lo = g.offsets[e] + g.tiles[TILE_REC * tile + 1];
   const int nrows = g.tiles[TILE_REC * tile + 2];
   switch ((nrows + 31) >> 5) {      // 32-row tiles of the chunk
-    case 1: gemm_chunk<SILU, 1, 3>(g, smem, ntile, e, row_lo, nrows); break;
-    case 2: gemm_chunk<SILU, 2, 3>(g, smem, ntile, e, row_lo, nrows); break;
-    case 3: gemm_chunk<SILU, 3, 3>(g, smem, ntile, e, row_lo, nrows); break;
-    case 4: gemm_chunk<SILU, 4, 3>(g, smem, ntile, e, row_lo, nrows); break;
-    case 5: gemm_chunk<SILU, 5, 2>(g, smem, ntile, e, row_lo, nrows); break;
-    case 6: gemm_chunk<SILU, 6, 2>(g, smem, ntile, e, row_lo, nrows); break;
-    case 7: gemm_chunk<SILU, 7, 2>(g, smem, ntile, e, row_lo, nrows); break;
-    default: gemm_chunk<SILU, 8, 2>(g, smem, ntile, e, row_lo, nrows); break;
+    case 1: gemm_chunk<SILU, 1, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 2: gemm_chunk<SILU, 2, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 3: gemm_chunk<SILU, 3, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 4: gemm_chunk<SILU, 4, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 5: gemm_chunk<SILU, 5, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 6: gemm_chunk<SILU, 6, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 7: gemm_chunk<SILU, 7, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    default: gemm_chunk<SILU, 8, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
   }
 }
 
