@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--no-prefill-from-host", action="store_true",
                     help="skip the prefill run that streams the experts from host memory")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
+    ap.add_argument("--fp32-tokens", type=int, default=64,
+                    help="tokens of the same layer held in fp32, the paper's full precision (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -218,6 +220,39 @@ def main() -> int:
                                     "bit_identical_to_resident": same}
         log(f"[bench] prefill: {prefill}")
 
+    # ---- the same layer shape in fp32 (the paper's "full precision"): twice the bytes per token
+    fp32 = None
+    if args.fp32_tokens > 0:
+        c32 = cfg.small(name="cfg2-shape-fp32-resident", dtype="f32")
+        t0 = time.time()
+        layer32 = synth.layer_weights(c32, 0)
+        X32_np = synth.tokens(c32, args.fp32_tokens)
+        log(f"[bench] generated {c32.name} in {time.time() - t0:.1f} s")
+        with harness.MoEStack(c32, [layer32]) as st32:
+            X32 = harness.to_device(X32_np)
+            Y32 = torch.empty_like(X32)
+            for t in range(min(8, args.fp32_tokens)):
+                B.odmoe_decode_step(st32.handle, X32[t], Y32[t], None, None, None)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for t in range(args.fp32_tokens):
+                B.odmoe_decode_step(st32.handle, X32[t], Y32[t], None, None, None)
+            torch.cuda.synchronize()
+            el32 = time.perf_counter() - t1
+            r_us, u_us, d_us = B.odmoe_time_decode_kernels(st32.handle, 0, X32, args.fp32_tokens, 2)
+            y0 = harness.from_device(Y32[0])
+        from oracle import moe_oracle as O32
+        y_ref, _, _ = O32.moe_layer(X32_np[0], layer32[0], layer32[1], layer32[2], c32.top_k)
+        ub32 = c32.top_k * 2 * c32.hidden * c32.ffn * 4
+        fp32 = {"workload": c32.name, "tokens": args.fp32_tokens,
+                "tokens_per_s": round(args.fp32_tokens / el32, 1),
+                "ffn_up_us": round(u_us, 2), "ffn_up_GBps": round(ub32 / u_us / 1e3, 1),
+                "ffn_down_us": round(d_us, 2), "ffn_down_GBps": round(ub32 / 2 / d_us / 1e3, 1),
+                "route_us": round(r_us, 2),
+                "token0_max_abs_err_vs_oracle": float(np.max(np.abs(y0.astype(np.float64) - y_ref)))}
+        del layer32
+        log(f"[bench] fp32: {fp32}")
+
     # ---- cacheless stacks, short runs (host-link roofline)
     def run_cacheless(c, layers_u, n_tok, x_rows):
         t0 = time.time()
@@ -354,7 +389,7 @@ def main() -> int:
                    "weights": "resident in HBM"},
         "expert_gemv_hbm_GBps": None if gemv_gbps is None else round(gemv_gbps, 1),
         "measured_ceilings": ceilings,
-        "roofline": roofline, "cacheless": cacheless, "cacheless_fine_grained": cacheless_fine,
+        "roofline": roofline, "full_precision_fp32": fp32, "cacheless": cacheless, "cacheless_fine_grained": cacheless_fine,
         "prefill": prefill, "sep_emulation": sep, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -643,8 +643,9 @@ hipError_t launch_up_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& src,
   const long total = (long)sh.k * sh.F;
   // one block per CU when the rows allow it: every wave streams one long contiguous run
   long rpw = (total + (long)num_cu() * nw - 1) / ((long)num_cu() * nw);
-  // small layers are latency bound: spread them over four times as many waves
-  if (rpw < 16) rpw = (total + (long)num_cu() * nw * 4 - 1) / ((long)num_cu() * nw * 4);
+  // small layers are latency bound: spread them over four times as many waves; so are rows of
+  // more than 8 chunks (a wave cannot keep a whole W1/W3 row pair in flight in its registers)
+  if (rpw < 16 || NCH > 8) rpw = (total + (long)num_cu() * nw * 4 - 1) / ((long)num_cu() * nw * 4);
   if (rpw < 1) rpw = 1;
   if (g_tune_up_rpw > 0) rpw = g_tune_up_rpw;
   const int grid = (int)((total + nw * rpw - 1) / (nw * rpw));
