@@ -7,6 +7,8 @@
 // touch the matrix cores.
 #include "kernels.h"
 
+#include <cstdlib>
+
 namespace odmoe {
 namespace {
 
@@ -573,7 +575,22 @@ constexpr size_t MAX_LDS = 160 * 1024;
 
 }  // namespace
 
+namespace {
+// Launch-shape overrides for tuning experiments (0 = use the built-in policy); read once from the
+// environment: ODMOE_TUNE_UP_RPW (rows per wave of the w1/w3 GEMV), ODMOE_TUNE_DOWN_RPB (rows
+// per block of the w2 GEMV), ODMOE_TUNE_DOWN_EG (its expert groups per block).
+int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0;
+int env_int(const char* name) {
+  const char* v = getenv(name);
+  const int n = v ? atoi(v) : 0;
+  return n > 0 ? n : 0;
+}
+}  // namespace
+
 hipError_t kernels_init() {
+  g_tune_up_rpw = env_int("ODMOE_TUNE_UP_RPW");
+  g_tune_down_rpb = env_int("ODMOE_TUNE_DOWN_RPB");
+  g_tune_down_eg = env_int("ODMOE_TUNE_DOWN_EG");
   hipError_t e;
   const int big = (int)MAX_LDS;
 #define ODMOE_SET_LDS(fn)                                                                    \
@@ -620,8 +637,6 @@ hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, con
 
 namespace {
 
-// Launch-shape overrides for tuning experiments (0 = use the built-in policy).
-int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0;
 
 int g_num_cu = 0;
 int num_cu() {
@@ -643,9 +658,13 @@ hipError_t launch_up_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& src,
   const long total = (long)sh.k * sh.F;
   // one block per CU when the rows allow it: every wave streams one long contiguous run
   long rpw = (total + (long)num_cu() * nw - 1) / ((long)num_cu() * nw);
-  // small layers are latency bound: spread them over four times as many waves; so are rows of
-  // more than 8 chunks (a wave cannot keep a whole W1/W3 row pair in flight in its registers)
-  if (rpw < 16 || NCH > 8) rpw = (total + (long)num_cu() * nw * 4 - 1) / ((long)num_cu() * nw * 4);
+  // Four times as many waves (16 per CU) where one wave per SIMD does not keep enough loads in
+  // flight: small layers (latency bound), rows of fewer than 8 chunks (a wave has 2*NCH loads of
+  // 1 KB in flight), and rows of more than 8 chunks whose vector still fits 64 registers (fp32: a
+  // wave cannot hold a whole W1/W3 row pair in flight, and its register count still allows four
+  // waves per SIMD).
+  constexpr bool more_waves = NCH < 8 || (NCH > 8 && NCH * DT<T>::VEC <= 64);
+  if (rpw < 16 || more_waves) rpw = (total + (long)num_cu() * nw * 4 - 1) / ((long)num_cu() * nw * 4);
   if (rpw < 1) rpw = 1;
   if (g_tune_up_rpw > 0) rpw = g_tune_up_rpw;
   const int grid = (int)((total + nw * rpw - 1) / (nw * rpw));
@@ -678,13 +697,17 @@ hipError_t launch_down_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& sr
   const int max_waves = CPW <= 4 ? 16 : 8;
   int n_eg = 1;
   if (nwb <= 2) n_eg = sh.k < max_waves / nwb ? sh.k : max_waves / nwb;
+  else if (nwb <= 4) n_eg = sh.k < 2 ? sh.k : 2;   // blocks of at least 6 waves keep enough loads in flight
   if (n_eg > 8) n_eg = 8;
   if (g_tune_down_eg > 0) n_eg = g_tune_down_eg;
+  if (n_eg > max_waves / nwb) n_eg = max_waves / nwb;   // block size limit of the kernel
+  if (n_eg > sh.k) n_eg = sh.k;
+  if (n_eg < 1) n_eg = 1;
   int rpb = (sh.H + num_cu() - 1) / num_cu();
-  if (n_eg > 1 && rpb > 4) rpb = 4;  // small layers: more, shorter blocks
+  if (n_eg > 1 && nwb <= 2 && rpb > 4) rpb = 4;  // small layers: more, shorter blocks
   rpb = (rpb + 1) & ~1;              // two rows in flight
   if (rpb > 64) rpb = 64;
-  if (g_tune_down_rpb > 0) rpb = g_tune_down_rpb;
+  if (g_tune_down_rpb > 0) rpb = (g_tune_down_rpb + 1) & ~1;
   const int grid = (sh.H + rpb - 1) / rpb;
   const int nw = nwb * n_eg;
   const size_t lds = (size_t)nw * rpb * sizeof(float);
