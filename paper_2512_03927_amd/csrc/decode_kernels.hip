@@ -610,7 +610,8 @@ hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, con
                              int32_t* idx_mirror, const void* const* table, int32_t table_off,
                              const void** eptr_out, const RouteScratch* scratch) {
   if (T <= 0) return hipSuccess;
-  if (scratch && scratch->logits && sh.E > 8 && T <= scratch->max_tokens) {
+  // (up to 32 experts, four rounds of one block cost less than the tickets of the spread variant)
+  if (scratch && scratch->logits && sh.E > 32 && T <= scratch->max_tokens) {
     const dim3 grid((sh.E + 7) / 8, T);
     if (sh.dtype == ODMOE_F32)
       route_topk_split_kernel<float><<<grid, 512, 0, s>>>(

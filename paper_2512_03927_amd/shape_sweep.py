@@ -1,0 +1,59 @@
+"""Decode-kernel timings over a range of MoE layer shapes (needs an MI355X).
+
+    python -m paper_2512_03927_amd.shape_sweep            # all shapes below
+    python -m paper_2512_03927_amd.shape_sweep 0 3 7      # a selection, by position
+
+For each shape one synthetic layer is generated and made resident, and the router, w1/w3 GEMV and
+w2 GEMV are timed with HIP events (odmoe_time_decode_kernels: each kernel launched back to back
+for 32 tokens); the GB/s figures are algorithmic bytes (the k chosen experts' W1|W3, resp. W2)
+over the kernel time.  The launch policies of the two GEMVs were chosen from this table.
+"""
+from __future__ import annotations
+
+import sys
+
+# hidden, ffn, experts held resident here (not the model's count where that is large), top_k, dtype
+SHAPES = [
+    (4096, 14336, 8, 2, "bf16"),    # Mixtral-8x7B layer (benchmark config 2)
+    (4096, 14336, 8, 2, "f32"),     # the same in fp32 (the paper's full precision)
+    (6144, 16384, 8, 2, "bf16"),
+    (8192, 8192, 8, 2, "bf16"),
+    (7168, 2048, 32, 8, "bf16"),    # many small experts on a wide hidden state
+    (5120, 1536, 32, 6, "bf16"),
+    (3072, 8192, 16, 2, "bf16"),
+    (2048, 8192, 8, 2, "bf16"),
+    (2048, 1408, 64, 6, "bf16"),    # fine-grained layer (benchmark config 5)
+    (2048, 1408, 64, 6, "f32"),
+    (2048, 768, 128, 8, "bf16"),
+    (1024, 4096, 16, 2, "bf16"),
+    (1024, 4096, 16, 2, "f32"),
+]
+
+
+def main(argv) -> int:
+    from . import binding as B
+    from . import harness, synth
+    sel = [int(a) for a in argv] or range(len(SHAPES))
+    n_tok = 32
+    for si in sel:
+        hd, f, e, k, dt = SHAPES[si]
+        cfg = synth.MoEConfig(f"sweep{si}", hd, f, e, k, dtype=dt, n_tokens=n_tok, seed=100 + si)
+        layer = synth.layer_weights(cfg, 0)
+        with harness.MoEStack(cfg, [layer]) as st:
+            x = harness.to_device(synth.tokens(cfg, n_tok))
+            best = None
+            for _ in range(3):
+                r, u, d = B.odmoe_time_decode_kernels(st.handle, 0, x, n_tok, 2)
+                if best is None or u + d < best[1] + best[2]:
+                    best = (r, u, d)
+        r, u, d = best
+        es = 4 if dt == "f32" else 2
+        up_b, down_b = k * 2 * hd * f * es, k * hd * f * es
+        print(f"{dt:4s} H{hd:<5d} F{f:<6d} E{e:<4d} k{k}: route {r:6.2f} us | w1/w3 {u:7.2f} us "
+              f"{up_b / u / 1e3:5.0f} GB/s | w2 {d:7.2f} us {down_b / d / 1e3:5.0f} GB/s", flush=True)
+        del layer
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main(sys.argv[1:]))

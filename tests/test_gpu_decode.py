@@ -101,8 +101,9 @@ def test_layer_parity_shapes(H, Hd, F, E, k, dtype):
 
 
 # ---------------------------------------------------------------- routing edge cases
-def test_routing_ties_zero_router_and_bias(H):
-    cfg = synth.MoEConfig("t", 256, 64, 12, 4, dtype="bf16", n_tokens=40, seed=5)
+@pytest.mark.parametrize("E", [12, 40])   # 40 experts: few-token calls take the multi-block router
+def test_routing_ties_zero_router_and_bias(H, E):
+    cfg = synth.MoEConfig("t", 256, 64, E, 4, dtype="bf16", n_tokens=40, seed=5)
     Wg, _, experts = synth.layer_weights(cfg)
     Wg = Wg.copy()
     Wg[7] = Wg[2]
