@@ -100,27 +100,33 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 
 // ---------------------------------------------------------------------------------------------
 // Grouped GEMM  C[p, n] = sum_k A[row(p), k] * W_e[n, k]  for one chunk (up to BMX = 256 rows) of
-// one expert e and BN = 128 weight rows.  Built around the weight stream, which is what bounds it:
+// one expert e and BN = 256 weight rows (two 128-row halves).  Built around the weight stream,
+// which is what bounds it:
 //   - one block takes all rows of the chunk, so an expert with up to 256 tokens reads its weights
-//     exactly once;
+//     exactly once; the chunks of a larger expert are started together on one XCD (see the block
+//     order in grouped_gemm_kernel) so that the second one finds the weight tile in L2;
 //   - global memory goes straight into LDS (global_load_lds_dwordx4: a wave fills 1 KB = 8 rows of
 //     128 bytes per instruction, every 128-byte line fully coalesced) in a ring of K-steps of
 //     BK = 64; no staging registers, one s_barrier per step, and the only vmcnt wait is for the
 //     step about to be used.  The ring holds 3 steps of 40 / 48 KB for up to 64 / 128 rows and 2
-//     steps of 64 KB for up to 256 rows (measured: a fourth step does not help; reading the
-//     row-major weights 128 bytes per row at a time caps the stream at about 5.4 TB/s, against
-//     6.4 TB/s for whole rows);
+//     steps of 56 / 64 KB for up to 192 / 256 rows (measured: deeper rings do not help: the CU's
+//     vector L1 keeps only about 125 128-byte requests in flight whatever is queued behind them);
+//   - blocks start their K loops at different steps (kt0): the rows of a row-major matrix lie a
+//     multiple of 4 KB apart, and blocks that walk K in lockstep keep hitting the same memory
+//     channels (weight stream alone: 4.8 TB/s in lockstep, 5.8 TB/s rotated);
 //   - LDS rows are 128 bytes; the 16-byte piece q of row r sits at slot q ^ (r & 7) (the lane
 //     that fills slot s of row r fetches piece s ^ (r & 7)), so the MFMA fragment reads are
 //     conflict-free;
-//   - 8 waves as 2 (M) x 4 (N, 32 columns of each 128-row half); a wave multiplies up to four
-//     32-row tiles by its two 32-column tiles (8 MFMAs per 6 fragment reads), which keeps LDS
-//     read traffic below MFMA time; 32-row tiles past the end of the chunk are skipped;
-//   - the 128-column-wide block tile also halves the activation traffic per weight byte.
+//   - 8 waves as 2 (M) x 4 (N, 32 columns of each 128-row half); the chunk's NT = ceil(rows/32)
+//     row tiles go alternately to the two M groups, and a wave multiplies its (up to four) row
+//     tiles by its two 32-column tiles (8 MFMAs per 6 fragment reads), which keeps LDS read
+//     traffic below MFMA time; NT is a template parameter, so the K loop has no per-tile branches
+//     except the wave-uniform test for the odd tile;
+//   - the 256-row-wide block tile also halves the activation traffic per weight byte.
 //   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+127; out = bf16( silu(A W1^T) * (A W3^T) )
 //   !SILU : halves = weight rows n0..n0+127 / n0+128..n0+255; out = fp32 partial sums for K range
 //           ksplit, [gridDim.z][rows, ldo]
-// grid: x = N tile, y = entry of the chunk list, z = K split.  K is a multiple of 64.
+// K is a multiple of 64.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ int lds_slot(int row, int piece) { return row * BK + ((piece ^ (row & 7)) << 3); }
 
