@@ -36,6 +36,7 @@ def _check_tokens(yn, Y, toks):
     (320, 576, 8, 2, 16, False),     # smallest batch that takes the grouped path; some experts idle
     (128, 192, 8, 3, 257, True),     # k = 3, odd token count
     (2048, 1408, 64, 6, 48, False),  # fine-grained layer shape, most experts see 0-10 tokens
+    (128, 192, 16, 4, 1500, True),   # 6000 token-slots: experts with 1-4 chunks each, about 35 chunks
 ])
 def test_prefill_matches_oracle(H, Hd, F, E, k, T, bias):
     cfg = synth.MoEConfig("t", Hd, F, E, k, dtype="bf16", n_tokens=T, router_bias=bias, seed=21)
