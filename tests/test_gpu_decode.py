@@ -241,6 +241,25 @@ def test_hints_change_timing_only(H):
             B.odmoe_time_expert_loads(st_res.handle, 1)          # resident mode has no loads
 
 
+def test_caller_supplied_copy_stream_gives_the_same_tokens(H):
+    """With a copy stream borrowed from the caller every expert copy goes through that one stream
+    (the library's own four-stream rotation is off): same output, same load count."""
+    import torch
+    cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=6, n_slots=4, dtype="bf16", n_tokens=3, glue=1, seed=19)
+    layers = _stack_layers(cfg)
+    X = synth.tokens(cfg)
+    cs = torch.cuda.Stream()
+    with H.MoEStack(cfg, layers) as st_own, H.MoEStack(cfg, layers, copy_stream=cs) as st_ext:
+        for t in range(cfg.n_tokens):
+            x = H.to_device(X[t])
+            y0, idx0, s0 = st_own.decode(x)
+            y1, idx1, s1 = st_ext.decode(x)
+            assert np.array_equal(H.from_device(y0), H.from_device(y1)) and np.array_equal(idx0, idx1)
+            assert s0.loads == s1.loads == cfg.n_layers * cfg.top_k
+            y2, _, s2 = st_ext.decode(x, pred=idx0)
+            assert np.array_equal(H.from_device(y2), H.from_device(y0)) and s2.hint_hits == s2.loads
+
+
 def test_hint_recall_is_what_was_planted(H):
     """Hints corrupted at a chosen rate: the output never changes, and the confirmed fraction
     (the paper's recall, Section 3.2) is exactly the fraction of hints left intact."""
