@@ -354,6 +354,10 @@ def main() -> int:
                     for aligned in (True, False):
                         r, _ = shadow.emulate(main_s, sh, xs0, args.sep_iters, aligned)
                         sep["mean_recall"][f"{kind}_{'aligned' if aligned else 'unaligned'}"] = round(float(np.mean(r)), 4)
+                    if kind == "int8":      # recall against the alignment period (Section 3.2, Fig. 6)
+                        sep["int8_recall_by_alignment_period"] = {
+                            str(per): round(float(np.mean(shadow.emulate(main_s, sh, xs0, args.sep_iters, True, per)[0])), 4)
+                            for per in (1, 2, 4, 8, 16)}
         sep["random_prefetch_expectation"] = cs.top_k / cs.n_experts
         log(f"[bench] sep emulation: {sep}")
 

@@ -67,21 +67,25 @@ def shadow_layers(cfg: synth.MoEConfig, layers: Sequence, kind: str) -> List:
     return out
 
 
-def emulate(main, shadow, x0, n_iter: int, aligned: bool):
+def emulate(main, shadow, x0, n_iter: int, aligned: bool, period: int = 1):
     """Runs `n_iter` emulated decode iterations.
 
     main, shadow: harness.MoEStack of the same shape (main may be cacheless).  x0: device tensor [H].
     Each iteration the shadow stack produces its routing for all layers, the main stack decodes
     with those as hints, and the main stack's output becomes the next input.  aligned=True
-    restarts the shadow from the main stack's input every iteration; otherwise it follows its
-    own outputs.  Returns (recall per iteration: list of float, final main output tensor).
+    restarts the shadow from the main stack's input every `period` iterations (the alignment
+    period of Section 3.2; 1 = every iteration) and lets it follow its own outputs in between;
+    aligned=False never realigns.  Returns (recall per iteration: list of float, final main
+    output tensor).
     """
+    if period < 1:
+        raise ValueError("period must be >= 1")
     L, k = main.cfg.n_layers, main.cfg.top_k
     x_main = x0
     x_shadow = x0
     recalls = []
-    for _ in range(n_iter):
-        y_s, idx_s, _ = shadow.decode(x_main if aligned else x_shadow)
+    for it in range(n_iter):
+        y_s, idx_s, _ = shadow.decode(x_main if (aligned and it % period == 0) else x_shadow)
         y_m, idx_m, st = main.decode(x_main, pred=idx_s)
         if main.cfg.n_slots > 0:
             hits = st.hint_hits

@@ -40,6 +40,15 @@ def test_shadow_stack_hints(H):
                     rec[(kind, aligned)] = r
                     # hints change timing only: the main chain ends in the same bits
                     assert np.array_equal(H.from_device(x_end), base[-1][0])
+                if kind == "int4":
+                    # alignment period: period 1 is the aligned run, a period longer than the run
+                    # is the free-running one, and iterations right after a realignment equal the
+                    # aligned run's (same input, same weights)
+                    assert shadow.emulate(main, sh, x0, n_iter, True, 1)[0] == rec[(kind, True)]
+                    assert shadow.emulate(main, sh, x0, n_iter, True, n_iter + 1)[0] == rec[(kind, False)]
+                    r4 = shadow.emulate(main, sh, x0, n_iter, True, 4)[0]
+                    assert r4[0::4] == rec[(kind, True)][0::4]
+                    rec[(kind, 4)] = r4
                 # recall bookkeeping against the oracle's definition, first iteration, aligned
                 _, idx_s, _ = sh.decode(x0)
                 _, idx_m, st = main.decode(x0, pred=idx_s)
@@ -48,7 +57,7 @@ def test_shadow_stack_hints(H):
                 assert st.reloads == L * k - st.hint_hits
     assert all(v == 1.0 for v in rec[("bf16", True)]) and all(v == 1.0 for v in rec[("bf16", False)])
     m = {key: float(np.mean(v)) for key, v in rec.items()}
-    print("mean recall:", {f"{k_}-{'aligned' if a else 'free'}": round(v, 3) for (k_, a), v in m.items()})
+    print("mean recall:", {f"{k_}-{a}": round(v, 3) for (k_, a), v in m.items()})
     assert m[("int8", True)] >= m[("int4", True)] > k / cfg.n_experts
     assert m[("int8", True)] > 0.8
     # without alignment the copy drifts: late iterations are worse than with alignment
