@@ -284,6 +284,20 @@ def main() -> int:
             B.odmoe_decode_step(stc.handle, xs[0], yc, idx_used, None, s)
         torch.cuda.synchronize()
         el_hint = time.perf_counter() - t1
+        # "late departure" (Section 3.2, Fig. 5): the predictor's hints for the first d layers
+        # arrive too late to be used; those layers load on demand, the rest ahead of time
+        late = {}
+        for d in (1, 2, 4, 8):
+            if d >= c.n_layers:
+                continue
+            pred = idx_used.copy()
+            pred[:d] = -1
+            n_l = max(2, n_tok // 4)
+            t2 = time.perf_counter()
+            for t in range(n_l):
+                B.odmoe_decode_step(stc.handle, xs[0], yc, pred, None, s)
+            torch.cuda.synchronize()
+            late[str(d)] = round((time.perf_counter() - t2) / n_l * 1e3, 3)
         s.t_step_ms = -1.0
         B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)        # one timed token for the breakdown
         # the same bytes copied with no kernels in between (wall clock, all copy streams)
@@ -322,6 +336,7 @@ def main() -> int:
                "resident_stack_ms_per_token": round(comp_ms, 3),
                "step_over_max_compute_load": round(step_ms / max(load_ms, comp_ms), 4),
                "ms_per_token_with_perfect_hints": round(el_hint / n_tok * 1e3, 3),
+               "ms_per_token_hints_missing_for_first_layers": late,
                "load_window": {"n_groups": n_groups, "t_M_ms": round(t_m, 4), "t_W_ms": round(t_w, 4),
                                "t_maxload_ms": round(window, 4), "t_load_per_layer_ms": round(t_load_layer, 4),
                                "io_bottlenecked": bool(t_load_layer > window)},
