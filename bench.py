@@ -353,6 +353,29 @@ def main() -> int:
         layers5 = [synth.layer_weights(c5, l) for l in range(2)]
         X5 = synth.tokens(c5, 4)
         cacheless_fine = run_cacheless(c5, layers5, 8 * args.cacheless_tokens, [X5[t] for t in range(4)])
+        # sensitivity to the number of HBM slots (the paper does not state one for this shape):
+        # S = k (no room to load ahead), 2k (the default), 4k
+        sens = {}
+        for S in (c5.top_k, 2 * c5.top_k, 4 * c5.top_k):
+            with harness.MoEStack(c5.small(n_slots=S), layers5, unique_layers=2) as sts:
+                x5 = harness.to_device(X5[0])
+                y5 = torch.empty_like(x5)
+                s5 = B.odmoe_stats()
+                ids5 = np.zeros((c5.n_layers, c5.top_k), np.int32)
+                B.odmoe_decode_step(sts.handle, x5, y5, None, ids5, s5)
+                res = {}
+                for name, pred in (("no_hints", None), ("perfect_hints", ids5)):
+                    B.odmoe_decode_step(sts.handle, x5, y5, pred, None, s5)
+                    torch.cuda.synchronize()
+                    t3 = time.perf_counter()
+                    n5 = max(4, 2 * args.cacheless_tokens)
+                    for _ in range(n5):
+                        B.odmoe_decode_step(sts.handle, x5, y5, pred, None, s5)
+                    torch.cuda.synchronize()
+                    res[name] = round((time.perf_counter() - t3) / n5 * 1e3, 3)
+                sens[str(S)] = res
+        cacheless_fine["ms_per_token_by_slot_count"] = sens
+        log(f"[bench] slot sensitivity: {sens}")
 
     # ---- emulated SEP predictor: a quantised shadow stack supplies the hints (qualitative only)
     sep = None

@@ -76,8 +76,8 @@ typedef struct {
   /* kernel / copy times are HIP-event times summed over the layers of one call; they are 0
      unless timing was asked for (see odmoe_decode_step) */
   float t_route_ms;    /* router GEMV + top-k gate kernel */
-  float t_load_ms;     /* host->HBM expert copies: sum of the copies' own durations (copies on
-                          different copy streams may overlap, so this can exceed wall time) */
+  float t_load_ms;     /* host->HBM expert copies: time during which at least one copy was in
+                          flight (copies on different copy streams overlap) */
   float t_ffn_up_ms;   /* w1/w3 GEMV + SiLU gate kernel */
   float t_ffn_down_ms; /* w2 GEMV + weighted combine kernel */
   float t_glue_ms;     /* inter-layer glue kernel */

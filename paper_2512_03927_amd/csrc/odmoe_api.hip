@@ -3,7 +3,9 @@
 // validates, schedules and enqueues.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <chrono>
+#include <utility>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -145,12 +147,22 @@ int check_layer(const odmoe_layer* h, int32_t layer) {
 int enqueue_load(odmoe_layer* h, int32_t layer, int32_t expert, int32_t slot, hipEvent_t t0 = nullptr,
                  hipEvent_t t1 = nullptr) {
   hipStream_t cs = h->copy_ring[h->next_copy++ % h->copy_ring.size()];
+  // The copy must come after the kernels that last read the slot and after an earlier copy into
+  // it (possibly on another stream, possibly never read).  Both are usually long done by now (the
+  // slot was used two layers ago): a wait is put on the stream only for an event that is still
+  // pending, because every wait costs the copy queue about 5 us even when it is already satisfied.
+  auto wait_if_pending = [&](hipEvent_t ev) -> hipError_t {
+    const hipError_t q = hipEventQuery(ev);
+    if (q == hipSuccess) return hipSuccess;
+    if (q != hipErrorNotReady) return q;
+    (void)hipGetLastError();  // "not ready" is an answer, not a failure
+    return hipStreamWaitEvent(cs, ev, 0);
+  };
   if (h->done_pending[slot]) {
-    HIP_TRY(hipStreamWaitEvent(cs, h->done_ev[slot], 0));
+    HIP_TRY(wait_if_pending(h->done_ev[slot]));
     h->done_pending[slot] = 0;
   }
-  // An earlier copy into this slot (possibly on another stream, possibly never read) comes first.
-  if (h->copied_once[slot] && h->copy_ring.size() > 1) HIP_TRY(hipStreamWaitEvent(cs, h->ready_ev[slot], 0));
+  if (h->copied_once[slot] && h->copy_ring.size() > 1) HIP_TRY(wait_if_pending(h->ready_ev[slot]));
   const void* src = h->expert_w[(size_t)layer * h->cfg.n_experts + expert];
   if (t0) HIP_TRY(hipEventRecord(t0, cs));
   HIP_TRY(hipMemcpyAsync(h->pool_mem + (size_t)slot * h->expert_bytes, src, h->expert_bytes,
@@ -697,11 +709,24 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
         HIP_TRY(hipEventElapsedTime(&ms, TE(l, 3), TE(l, 4)));
         stats->t_glue_ms += ms;
       }
-      for (size_t i = 0; i < n_lev; i += 2) {
-        float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, h->lev[i], h->lev[i + 1]));
-        stats->t_load_ms += ms;
+      // time during which at least one expert copy was in flight: union of the copies'
+      // [begin, end] intervals (they overlap when they run on different copy streams)
+      std::vector<std::pair<float, float>> iv;
+      for (size_t i = 0; i + 1 < n_lev; i += 2) {
+        float b = 0.f, e = 0.f;
+        if (i) HIP_TRY(hipEventElapsedTime(&b, h->lev[0], h->lev[i]));
+        HIP_TRY(hipEventElapsedTime(&e, h->lev[0], h->lev[i + 1]));
+        iv.emplace_back(b, e);
       }
+      std::sort(iv.begin(), iv.end());
+      float cur_b = 0.f, cur_e = 0.f;
+      bool open = false;
+      for (const auto& p : iv) {
+        if (!open) { cur_b = p.first; cur_e = p.second; open = true; continue; }
+        if (p.first > cur_e) { stats->t_load_ms += cur_e - cur_b; cur_b = p.first; cur_e = p.second; }
+        else if (p.second > cur_e) cur_e = p.second;
+      }
+      if (open) stats->t_load_ms += cur_e - cur_b;
     }
     stats->h2d_bytes = n_loads * h->expert_bytes;
     stats->loads = n_loads;
