@@ -79,6 +79,9 @@ SHAPES = [
     (4096, 14336, 8, 2, "bf16"),    # the Mixtral layer shape (configs 2-4)
     (64, 64, 1024, 8, "bf16"),      # the most experts and the largest top-k the library takes
     (64, 64, 1, 1, "f32"),          # a single expert
+    (256, 8192, 4, 2, "bf16"),      # w2 rows of 16 chunks: four column slices x two expert groups per block
+    (4096, 256, 4, 2, "f32"),       # fp32 rows of 16 register chunks (16 waves per CU in the w1/w3 GEMV)
+    (6144, 64, 4, 2, "bf16"),       # bf16 rows of 12 register chunks
 ]
 
 
