@@ -149,6 +149,32 @@ def test_routing_ties_zero_router_and_bias(H, E):
         assert (H.from_device(st.ffn(0, i0, g0, x0)) == 0).all()
 
 
+def test_multi_block_router_is_repeatable(H):
+    """The router variant that spreads a token's experts over several blocks relies on a ticket
+    counter that every launch leaves at zero: many launches in a row, with varying token counts,
+    keep giving the bits of the one-block-per-token variant (which batches of more than 16 tokens
+    take), and so does a launch that follows other work on the stream."""
+    import torch
+    cfg = synth.MoEConfig("t", 512, 64, 96, 6, dtype="bf16", n_tokens=48, seed=6)
+    Wg, _, experts = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    with H.MoEStack(cfg, [(Wg, None, experts)]) as st:
+        xd = H.to_device(X)
+        idx_ref, gate_ref = st.route(0, xd)                      # 48 tokens: one block per token
+        idx_ref, gate_ref = idx_ref.cpu(), gate_ref.cpu()
+        r = np.random.default_rng(1)
+        outs = []
+        for it in range(300):
+            n = int(r.integers(1, 17))
+            lo = int(r.integers(0, cfg.n_tokens - n + 1))
+            outs.append((lo, n, st.route(0, xd[lo:lo + n].contiguous())))
+            if it % 50 == 49:
+                st.ffn(0, outs[-1][2][0], outs[-1][2][1], xd[lo:lo + n].contiguous())
+        torch.cuda.synchronize()
+        for lo, n, (i2, g2) in outs:
+            assert torch.equal(i2.cpu(), idx_ref[lo:lo + n]) and torch.equal(g2.cpu(), gate_ref[lo:lo + n])
+
+
 def test_identical_experts_make_routing_irrelevant(H):
     cfg = synth.MoEConfig("t", 128, 256, 6, 3, dtype="f32", n_tokens=3, seed=8)
     Wg, _, experts = synth.layer_weights(cfg)
