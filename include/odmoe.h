@@ -139,20 +139,22 @@ int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert);
  *   idx_dev[T,k], gate_dev[T,k], x_dev[T,H], y_dev[T,H] are device pointers.
  *   idx_host   optional host copy of idx (cacheless mode needs to know the experts on the
  *              host; when NULL there, the library reads idx_dev back and blocks for it).
- *   n_tokens   < 16: one fused w1/w3+SiLU GEMV and one w2+combine GEMV per token;
- *              >= 16 (resident, bf16, hidden and ffn multiples of 64): prefill path of
- *              Section 3.3 -- tokens are grouped by expert and each expert runs a grouped GEMM
- *              on the matrix cores; the SwiGLU intermediate is rounded to bf16 there (the
- *              matrix cores take bf16 operands).  Other shapes fall back to the per-token path.
+ *   n_tokens   resident mode: token by token (one fused w1/w3+SiLU GEMV and one w2+combine GEMV
+ *              per token) while the token-slots do not outnumber the experts
+ *              (n_tokens * top_k <= n_experts and n_tokens < 16); larger batches (bf16, hidden and
+ *              ffn multiples of 64) take the prefill path of Section 3.3 -- tokens are grouped by
+ *              expert and each expert runs a grouped GEMM on the matrix cores, reading its
+ *              weights once; the SwiGLU intermediate is rounded to bf16 there (the matrix cores
+ *              take bf16 operands).  Other shapes stay on the per-token path.
  *   evict_after  cacheless mode: nonzero releases the experts' slots after the kernels that
  *              read them (the paper's prompt eviction).  Ignored in resident mode.
  * Cacheless mode: n_tokens == 1 needs every chosen expert loading or ready (ESTATE otherwise);
- * the compute stream waits (stream side) for each copy.  n_tokens >= 16 (bf16, hidden and ffn
- * multiples of 64) is the prefill of Section 3.3 from host memory: the call itself streams
- * every expert that received tokens into a slot exactly once (experts already loading or
- * ready are used as they are), runs that expert's grouped GEMMs when its copy has landed, and
- * with evict_after releases the slot for the next expert, so that copies overlap GEMMs.
- * 1 < n_tokens < 16 is EINVAL in cacheless mode.
+ * the compute stream waits (stream side) for each copy.  n_tokens >= 2 (bf16, hidden and ffn
+ * multiples of 64; EINVAL otherwise) is the prefill of Section 3.3 from host memory: the call
+ * itself streams every expert that received tokens into a slot exactly once (experts already
+ * loading or ready are used as they are), runs that expert's grouped GEMMs when its copy has
+ * landed, and with evict_after releases the slot for the next expert, so that copies overlap
+ * GEMMs.
  */
 int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev,
                      const float* gate_dev, const int32_t* idx_host, const void* x_dev,

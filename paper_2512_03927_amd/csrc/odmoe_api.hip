@@ -502,7 +502,9 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
     ExpertSrc src{};
     src.table = h->table_dev;
     src.table_off = layer * E;
-    if (n_tokens >= 16 && prefill_supported(h->sh)) {
+    // Tokens grouped by expert read each expert once; token by token reads k experts per token:
+    // grouping pays as soon as the token-slots outnumber the experts (and always from 16 tokens).
+    if ((n_tokens >= 16 || (int64_t)n_tokens * k > E) && prefill_supported(h->sh)) {
       if ((rc = ensure_prefill_ws(h, n_tokens))) return rc;
       HIP_TRY(launch_prefill(h->compute, h->sh, h->table_dev, layer * E, idx_dev, gate_dev, x_dev,
                              n_tokens, y_dev, h->prefill_ws, h->prefill_ws_bytes));
@@ -520,7 +522,7 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
   // streamed from host memory into a slot exactly once, its grouped GEMMs run as soon as its
   // copy has landed, and the slot is handed to the next expert: with S >= 2 slots the copy of
   // the next expert overlaps the GEMMs of the current one.
-  if (n_tokens >= 16) {
+  if (n_tokens >= 2) {
     if (!prefill_supported(h->sh))
       return fail(ODMOE_EINVAL, "cacheless batches need bf16 and hidden/ffn multiples of 64");
     if ((rc = ensure_prefill_ws(h, n_tokens))) return rc;
@@ -560,8 +562,7 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
     return ODMOE_OK;
   }
 
-  // cacheless decode
-  if (n_tokens != 1) return fail(ODMOE_EINVAL, "cacheless mode computes one token, or a batch of >= 16, per call");
+  // cacheless decode (n_tokens == 1)
   int32_t ids[ODMOE_MAX_TOPK];
   if (idx_host) {
     memcpy(ids, idx_host, k * sizeof(int32_t));
