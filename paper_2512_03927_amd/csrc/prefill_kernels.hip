@@ -437,15 +437,20 @@ hipError_t ensure_attrs() {
   return hipSuccess;
 }
 
-// K split of the w2 GEMM: few output tiles but a long K, so K is cut until the grid fills the chip.
-void w2_split(const Shape& sh, int* n_split, int* k_per_split) {
+// K split of the w2 GEMM: few output tiles but a long K, so K is cut until the grid has about two
+// blocks per CU, counting one chunk per expert that can have tokens (every split writes and the
+// combine re-reads a full fp32 copy of the output, so no finer than that, and at least 8 K-steps
+// per block).  A function of the shape and the token count only: the GEMM and the combine agree.
+void w2_split(const Shape& sh, int32_t T, int* n_split, int* k_per_split) {
   const int nt2 = (sh.H + BN - 1) / BN;
   const int ksteps = sh.F / BK;
-  int ns = (4 * 256 + nt2 * 8 - 1) / (nt2 * 8);   // aim for >= 1024 blocks at ~8 chunks
+  const long slots = (long)T * sh.k;
+  const long chunks = slots < sh.E ? slots : sh.E;
+  long ns = (2 * 256 + nt2 * chunks - 1) / (nt2 * chunks);
   if (ns > MAX_KSPLIT) ns = MAX_KSPLIT;
-  if (ns > ksteps) ns = ksteps;
+  if (ns > ksteps / 8) ns = ksteps / 8;
   if (ns < 1) ns = 1;
-  *k_per_split = ((ksteps + ns - 1) / ns) * BK;
+  *k_per_split = (int)((ksteps + ns - 1) / ns) * BK;
   *n_split = (sh.F + *k_per_split - 1) / *k_per_split;
 }
 
@@ -486,7 +491,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   if (e != hipSuccess) return e;
 
   int n_split, k_per_split;
-  w2_split(sh, &n_split, &k_per_split);
+  w2_split(sh, T, &n_split, &k_per_split);
   GemmArgs g2{};
   g2.A = c.hbuf; g2.lda = sh.F; g2.a_slot = nullptr; g2.slot_div = 1;
   g2.table = table; g2.table_off = table_off; g2.expert_override = expert_override; g2.tile_first = tile_first;
@@ -503,7 +508,7 @@ hipError_t prefill_combine(hipStream_t s, const Shape& sh, const float* gate, in
                            void* workspace) {
   const Carve c = carve(sh, T, workspace);
   int n_split, k_per_split;
-  w2_split(sh, &n_split, &k_per_split);
+  w2_split(sh, T, &n_split, &k_per_split);
   combine_kernel<<<dim3(T, (sh.H + 1023) / 1024), 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split,
                                    (size_t)T * sh.k * sh.H);
   return hipGetLastError();
