@@ -69,3 +69,14 @@ def test_load_window_matches_oracle_and_worked_example():
     assert abs(B.odmoe_load_window_ms(4, 1.0, 1.0) - 7.0) < 1e-12        # 4 t^M + 3 t^W
     assert B.odmoe_load_window_ms(0, 1.0, 1.0) == 0.0
     assert B.odmoe_slot_groups(None) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more exits with a message (no GPU is touched)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
