@@ -98,9 +98,11 @@ typedef struct {
  *               n_slots == 0: DEVICE pointers.  n_slots > 0: HOST pointers to PINNED memory
  *               (hipHostMalloc / torch pin_memory; odmoe_pinned_alloc provides it too).
  *   compute_stream  hipStream_t as void*; NULL = the null stream.
- *   copy_stream     hipStream_t for host->HBM copies; NULL = the library creates four and rotates
- *                   the copies over them (back-to-back copies on one stream leave gaps that
- *                   cost about 4 % of the link rate for 17 MB experts).
+ *   copy_stream     hipStream_t for host->HBM copies; NULL = the library creates four and
+ *                   rotates the copies over them, over three of them for copies issued ahead
+ *                   of time from hints (back-to-back copies on one stream leave gaps that cost
+ *                   about 4 % of the link rate for 17 MB experts; with four streams the copies
+ *                   of consecutive layers no longer finish in issue order).
  *   out         receives the handle.
  * Allocates S*expert_bytes of HBM for the slot pool plus small scratch.  n_slots > 0 needs
  * n_slots >= top_k.  Returns EINVAL / ENOMEM / EHIP; on failure *out is NULL.

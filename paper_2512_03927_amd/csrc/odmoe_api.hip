@@ -8,6 +8,7 @@
 #include <utility>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -66,6 +67,8 @@ struct odmoe_layer {
   // copies on one stream leave a gap of about 10 us between them, which matters for small experts.
   std::vector<hipStream_t> copy_ring;
   uint32_t next_copy = 0;
+  uint32_t ring_active = 0;   // streams the rotation uses (0 = all)
+  bool ring_fixed = false;    // the environment fixed the number of copy streams
 
   // scratch
   float* hbuf = nullptr;      // [k*F] fp32
@@ -146,7 +149,8 @@ int check_layer(const odmoe_layer* h, int32_t layer) {
 // Enqueue the copy of (layer, expert) into `slot` on the copy stream.
 int enqueue_load(odmoe_layer* h, int32_t layer, int32_t expert, int32_t slot, hipEvent_t t0 = nullptr,
                  hipEvent_t t1 = nullptr) {
-  hipStream_t cs = h->copy_ring[h->next_copy++ % h->copy_ring.size()];
+  const size_t n_ring = (h->ring_active && h->ring_active < h->copy_ring.size()) ? h->ring_active : h->copy_ring.size();
+  hipStream_t cs = h->copy_ring[h->next_copy++ % n_ring];
   // The copy must come after the kernels that last read the slot and after an earlier copy into
   // it (possibly on another stream, possibly never read).  Both are usually long done by now (the
   // slot was used two layers ago): a wait is put on the stream only for an event that is still
@@ -417,7 +421,20 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
       h->copy_ring.push_back(h->copy);
     } else {
       h->own_copy = true;
-      for (int i = 0; i < 4; ++i) {
+      // Four streams, of which copies issued ahead of time (with hints) rotate over three: enough
+      // concurrent copies to close the gaps between them, few enough that they still complete
+      // roughly in issue order (with four, the experts of two consecutive top-2 layers load side
+      // by side and finish together, after which both layers compute while the link idles).
+      // ODMOE_COPY_STREAMS=1..8 fixes the number for every case.
+      int n_copy_streams = 4;
+      if (const char* v = getenv("ODMOE_COPY_STREAMS")) {
+        const int n = atoi(v);
+        if (n >= 1 && n <= 8) {
+          n_copy_streams = n;
+          h->ring_fixed = true;
+        }
+      }
+      for (int i = 0; i < n_copy_streams; ++i) {
         hipStream_t cs = nullptr;
         INIT_TRY(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking), ODMOE_EHIP);
         h->copy_ring.push_back(cs);
@@ -609,6 +626,7 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
 
   uint64_t n_loads = 0, n_reloads = 0, n_hits = 0;
   if (h->sched) h->sched->begin_token(predicted_idx_host);
+  if (!h->ring_fixed) h->ring_active = predicted_idx_host ? 3 : 0;
   std::vector<Action> acts;
   int rc;
 
