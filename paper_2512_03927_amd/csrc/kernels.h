@@ -64,9 +64,10 @@ hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* tab
                           int32_t T, void* y, void* workspace, size_t workspace_bytes);
 // The same in phases, for experts that are streamed in one at a time: bucket the token-slots;
 // run both GEMMs for the chunk-list entries [tile_first, tile_first + tile_count) with the weights
-// at expert_override (or from the table when null); combine.  Chunk-list entries are ordered by
-// expert; prefill_chunks_of(count) is the number of entries of an expert with `count` token-slots.
-// A range given to prefill_gemms must hold all entries of each expert it touches.
+// at expert_override (or from the table when null); combine.  The chunk list holds the experts
+// in the order prefill_expert_order gives for their token-slot counts (count[E] -> order[E]: by
+// count, the larger half interleaved with the smaller half), each with prefill_chunks_of(count)
+// entries.  A range given to prefill_gemms must hold all entries of each expert it touches.
 hipError_t prefill_sort(hipStream_t s, const Shape& sh, const int32_t* idx, int32_t T, void* workspace,
                         size_t workspace_bytes);
 hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* table, int32_t table_off,
@@ -75,6 +76,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
 hipError_t prefill_combine(hipStream_t s, const Shape& sh, const float* gate, int32_t T, void* y,
                            void* workspace);
 int prefill_chunks_of(int32_t count);
+void prefill_expert_order(const int32_t* count, int32_t E, int32_t* order);
 
 // Plain streaming kernel over `bytes` (multiple of 16): mode 0 copies src to dst, mode 1 only
 // reads src (dst: 4 bytes of scratch).

@@ -555,8 +555,11 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
     for (size_t i = 0; i < n; ++i)
       if (ids_all[i] >= 0 && ids_all[i] < E) ++count[ids_all[i]];
     HIP_TRY(prefill_sort(h->compute, h->sh, idx_dev, n_tokens, h->prefill_ws, h->prefill_ws_bytes));
+    std::vector<int32_t> order(E);
+    prefill_expert_order(count.data(), E, order.data());   // the order of the device's chunk list
     int tile_first = 0;
-    for (int e = 0; e < E; ++e) {
+    for (int p = 0; p < E; ++p) {
+      const int e = order[p];
       const int tiles_e = prefill_chunks_of(count[e]);
       if (tiles_e == 0) continue;
       int s = h->pool->find(layer, e);

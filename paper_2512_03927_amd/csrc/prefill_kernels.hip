@@ -53,6 +53,7 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
                                                            int32_t* __restrict__ n_tiles) {
   __shared__ int32_t cnt[ODMOE_MAX_EXPERTS];
   __shared__ int32_t start[ODMOE_MAX_EXPERTS + 1];
+  __shared__ int32_t order[ODMOE_MAX_EXPERTS];
   for (int e = threadIdx.x; e < E; e += blockDim.x) cnt[e] = 0;
   __syncthreads();
   for (int s = threadIdx.x; s < n; s += blockDim.x) {
@@ -60,11 +61,29 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
     if (e >= 0 && e < E) atomicAdd(&cnt[e], 1);
   }
   __syncthreads();
+  // Order in which the experts' chunks are listed (= dispatched): experts ranked by token count,
+  // the larger half interleaved with the smaller half (1st, (E/2+1)th, 2nd, ...).  Large chunks are
+  // bound by the matrix cores and the fills, small ones by the weight stream; running them side by
+  // side is faster than either sorted order, and the smallest experts end the launch.
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    const int c = cnt[e];
+    int rank = 0;
+    for (int j = 0; j < E; ++j) rank += (cnt[j] > c) || (cnt[j] == c && j < e);
+    const int half = (E + 1) / 2;
+    order[rank < half ? 2 * rank : 2 * (rank - half) + 1] = e;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
     int run = 0, nt = 0;
     for (int e = 0; e < E; ++e) {
       start[e] = run;
       offsets[e] = run;
+      run += cnt[e];
+    }
+    start[E] = run;
+    offsets[E] = run;
+    for (int p = 0; p < E; ++p) {
+      const int e = order[p];
       const int nch = (cnt[e] + BMX - 1) / BMX;
       const int per = nch ? (cnt[e] + nch - 1) / nch : 0;
       const int first = nt;
@@ -77,10 +96,7 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
         tl[4] = nch;
         ++nt;
       }
-      run += cnt[e];
     }
-    start[E] = run;
-    offsets[E] = run;
     *n_tiles = nt;
   }
   __syncthreads();
@@ -416,6 +432,15 @@ bool prefill_supported(const Shape& sh) {
 }
 
 size_t prefill_workspace_bytes(const Shape& sh, int32_t T) { return carve(sh, T, nullptr).total; }
+
+void prefill_expert_order(const int32_t* count, int32_t E, int32_t* order) {
+  const int half = (E + 1) / 2;
+  for (int e = 0; e < E; ++e) {
+    int rank = 0;
+    for (int j = 0; j < E; ++j) rank += (count[j] > count[e]) || (count[j] == count[e] && j < e);
+    order[rank < half ? 2 * rank : 2 * (rank - half) + 1] = e;
+  }
+}
 
 int prefill_chunks_of(int32_t count) {
   if (count <= 0) return 0;
