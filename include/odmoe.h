@@ -177,8 +177,9 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev,
  *   stats      NULL, or receives counters; kernel/copy times are measured only when
  *              stats->t_step_ms is set to a negative value on entry (adds event overhead).
  * Blocks until y is complete, except in resident mode with idx_out_host == NULL and
- * stats == NULL, where the call only enqueues work on the compute stream (and no host
- * synchronisation happens per layer either).
+ * stats == NULL, where the call only enqueues kernels on the compute stream (no host
+ * synchronisation per layer, no allocation, no fill or copy by the runtime): in that form a
+ * call can be recorded into a HIP graph captured on the compute stream and replayed.
  */
 int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
                       const int32_t* predicted_idx_host, int32_t* idx_out_host,

@@ -371,6 +371,38 @@ def test_error_paths(H):
         assert ei.value.code == B.ODMOE_EINVAL
 
 
+def test_resident_decode_step_can_be_captured_in_a_graph(H):
+    """Resident mode with nothing to report enqueues kernels only (no allocation, no fill by the
+    runtime, no host wait), so a decode step can be recorded into a HIP graph on the handle's
+    compute stream.  Every replay, with eager steps and synchronisations in between and the input
+    buffer rewritten in place, gives the bits of the eager step."""
+    import torch
+    cfg = synth.MoEConfig("t", 256, 512, 40, 4, n_layers=5, n_slots=0, dtype="bf16", n_tokens=4, glue=1, seed=23)
+    layers = _stack_layers(cfg)
+    X = synth.tokens(cfg)
+    from paper_2512_03927_amd import binding as B
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with H.MoEStack(cfg, layers) as st:                  # the handle's compute stream is `side`
+            x = H.to_device(X[0])
+            y_eager, y_graph = torch.empty_like(x), torch.empty_like(x)
+            B.odmoe_decode_step(st.handle, x, y_eager, None, None, None)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                B.odmoe_decode_step(st.handle, x, y_graph, None, None, None)
+            for t in range(cfg.n_tokens):
+                x.copy_(H.to_device(X[t]))
+                B.odmoe_decode_step(st.handle, x, y_eager, None, None, None)
+                side.synchronize()
+                y_graph.zero_()
+                g.replay()
+                side.synchronize()
+                assert torch.equal(y_eager, y_graph), f"replay {t}"
+                assert float(y_graph.float().abs().max()) > 0
+            del g
+
+
 def test_glue_zero_chains_y(H):
     cfg = synth.MoEConfig("t", 128, 128, 4, 2, n_layers=3, n_slots=0, dtype="f32", n_tokens=1, glue=0, w_std=0.1)
     layers = _stack_layers(cfg)
