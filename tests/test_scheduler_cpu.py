@@ -143,3 +143,49 @@ def test_slot_pool_fifo_and_errors(sim):
     assert sim.odmoe_sim_pool_acquire(h, 0, 5) == 1 and sim.odmoe_sim_pool_acquire(h, 0, 6) == 0
     assert sim.odmoe_sim_pool_release(h, 7) == -1
     sim.odmoe_sim_del(h)
+
+
+def test_any_hints_keep_the_invariants():
+    """Property test: whatever the hints hold (right, wrong, duplicated, out of range), the
+    invariants checked in run_token hold, every load is either used or dropped, and nothing is
+    counted twice."""
+    from hypothesis import given, settings, strategies as st
+
+    path = os.path.join(PKG, "libodmoe_hostsim.so")
+    lib = C.CDLL(path)
+    lib.odmoe_sim_new.restype = C.c_void_p
+    lib.odmoe_sim_new.argtypes = [C.c_int] * 4
+
+    @st.composite
+    def case(draw):
+        E = draw(st.integers(1, 12))
+        k = draw(st.integers(1, min(E, 4)))
+        S = draw(st.integers(k, 4 * k))
+        L = draw(st.integers(1, 9))
+        seed = draw(st.integers(0, 2 ** 31 - 1))
+        mode = draw(st.sampled_from(["perfect", "noisy", "garbage"]))
+        return L, E, k, S, seed, mode
+
+    @settings(max_examples=300, deadline=None)
+    @given(case())
+    def check(c):
+        L, E, k, S, seed, mode = c
+        r = np.random.default_rng(seed)
+        actual = np.stack([r.permutation(E)[:k] for _ in range(L)]).astype(np.int32)
+        pred = actual.copy()
+        if mode == "noisy":
+            mask = r.random(pred.shape) < 0.4
+            pred[mask] = r.integers(0, E, size=int(mask.sum()))          # may duplicate within a layer
+        elif mode == "garbage":
+            pred = r.integers(-3, E + 3, size=pred.shape).astype(np.int32)
+        log, (loads, reloads, hits) = run_token(lib, L, E, k, S, actual, np.ascontiguousarray(pred))
+        drops = sum(1 for a in log if a[0] == DROP)
+        releases = sum(1 for a in log if a[0] == RELEASE)
+        assert releases == L * k and loads - drops == L * k
+        assert hits + reloads <= L * k and reloads <= loads
+        if mode == "perfect":
+            assert drops == 0 and reloads == 0 and loads == L * k
+            if S >= 2 * k:
+                assert hits == L * k
+
+    check()
