@@ -178,6 +178,7 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   constexpr int MTW = (NT + 1) / 2;                     // 32-row tiles per wave: tiles wm, wm+2, wm+4, ...
   constexpr int B_INSTR = BN / 64;                      // B fills per wave per K-step
   constexpr int LPS = A_INSTR + B_INSTR;                // DMA loads per wave per K-step
+  constexpr bool ODD_NT = (NT & 1) != 0;                // the last 64-row group is half used
   constexpr size_t A_STAGE = (size_t)A_ROWS * BK;
   constexpr size_t STAGE = A_STAGE + (size_t)BN * BK;
   static_assert(NSTAGE * STAGE * sizeof(bf16_t) <= GEMM_LDS, "ring does not fit");
@@ -231,8 +232,9 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
     const int ko = step_offset(kt);
 #pragma unroll
     for (int i = 0; i < A_INSTR; ++i)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(a_src[i] + ko),
-                                       (lds_void_ptr)(sa + (i * 8 + wave) * 8 * BK), 16, 0, 0);
+      if (i + 1 < A_INSTR || !ODD_NT || wave < 4)   // odd tile count: the last fill covers 32 rows only
+        __builtin_amdgcn_global_load_lds((global_void_ptr)(a_src[i] + ko),
+                                         (lds_void_ptr)(sa + (i * 8 + wave) * 8 * BK), 16, 0, 0);
   };
   auto issue_b = [&](int stage, int kt) {
     bf16_t* sa = smem + stage * STAGE;
@@ -266,7 +268,10 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   }
   int stage = 0, refill = NSTAGE - 1;
   for (int kt = 0; kt < nk; ++kt) {
-    ODMOE_VMCNT((NSTAGE - 2) * LPS);   // this wave's fills of step kt have landed (later steps may fly)
+    // this wave's fills of step kt have landed (those of later steps may still fly; with an odd
+    // tile count waves 4..7 issue one fill fewer per step)
+    if (ODD_NT && wave >= 4) ODMOE_VMCNT((NSTAGE - 2) * (LPS - 1));
+    else ODMOE_VMCNT((NSTAGE - 2) * LPS);
     __builtin_amdgcn_s_barrier();      // ... and everybody else's; everybody is done with step kt-1
     const int nxt = kt + NSTAGE - 1 < last ? kt + NSTAGE - 1 : last;
     if (!SPLIT_ISSUE) issue_a(refill, nxt);            // refill the buffer that step kt-1 used
