@@ -412,6 +412,8 @@ struct Carve {
   size_t total;
 };
 
+void w2_split(const Shape& sh, int32_t T, int* n_split, int* k_per_split);
+
 Carve carve(const Shape& sh, int32_t T, void* base) {
   const size_t n = (size_t)T * sh.k;
   const size_t max_tiles = (size_t)sh.E + (n + BMX - 1) / BMX;
@@ -425,7 +427,9 @@ Carve carve(const Shape& sh, int32_t T, void* base) {
   c.tiles = reinterpret_cast<int32_t*>(take(TILE_REC * max_tiles * sizeof(int32_t)));
   c.n_tiles = reinterpret_cast<int32_t*>(take(sizeof(int32_t)));
   c.hbuf = reinterpret_cast<bf16_t*>(take(n * sh.F * sizeof(bf16_t)));
-  c.ybuf = reinterpret_cast<float*>(take((size_t)MAX_KSPLIT * n * sh.H * sizeof(float)));
+  int n_split = 1, k_per_split = 0;
+  w2_split(sh, T, &n_split, &k_per_split);
+  c.ybuf = reinterpret_cast<float*>(take((size_t)n_split * n * sh.H * sizeof(float)));
   c.total = off;
   return c;
 }
