@@ -264,6 +264,7 @@ def main() -> int:
         for _ in range(2):                                               # warm-up tokens
             B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)
         torch.cuda.synchronize()
+        yc_first = yc.clone()
         t_start = time.perf_counter()
         loads = 0
         per_token = []
@@ -339,6 +340,20 @@ def main() -> int:
                 B.odmoe_decode_step(str_.handle, xs[t % len(xs)], yr, None, None, None)
             torch.cuda.synchronize()
             comp_ms = (time.perf_counter() - t2) / n_res * 1e3
+        # experts read in place: the same pinned buffers, no slot pool, no copies; the GEMV kernels
+        # pull the activated experts' weights across the host link while they compute
+        with harness.MoEStack(c.small(n_slots=0), layers_u, unique_layers=len(layers_u),
+                              experts_in_host_memory=True, buffers_of=stc) as sth:
+            yh = torch.empty_like(xs[0])
+            B.odmoe_decode_step(sth.handle, xs[0], yh, None, None, None)
+            torch.cuda.synchronize()
+            same_bits = bool(torch.equal(yh, yc_first))
+            n_inp = max(2, n_tok // 3)
+            t2 = time.perf_counter()
+            for t in range(n_inp):
+                B.odmoe_decode_step(sth.handle, xs[t % len(xs)], yh, None, None, None)
+            torch.cuda.synchronize()
+            inplace_ms = (time.perf_counter() - t2) / n_inp * 1e3
         step_ms = el / n_tok * 1e3
         # load-window check of the paper (Section 3.1): per layer, t^M = router + glue (the stand-in
         # for the main node's work), t^W = expert FFN, against the time to load one layer's k experts
@@ -360,6 +375,11 @@ def main() -> int:
                "resident_stack_ms_per_token": round(comp_ms, 3),
                "step_over_max_compute_load": round(step_ms / max(load_ms, comp_ms), 4),
                "ms_per_token_with_perfect_hints": round(el_hint / n_tok * 1e3, 3),
+               "experts_read_in_place": {"ms_per_token": round(inplace_ms, 3),
+                                         "tokens_per_s": round(1e3 / inplace_ms, 4),
+                                         "link_GBps": round(c.n_layers * c.top_k * c.expert_bytes / inplace_ms / 1e6, 2),
+                                         "over_copy_only": round(inplace_ms / load_ms, 4),
+                                         "hbm_expert_bytes": 0, "same_output_bits_as_slot_pool": same_bits},
                "ms_per_token_hints_missing_for_first_layers": late,
                "by_hint_miss_rate": by_recall,
                "load_window": {"n_groups": n_groups, "t_M_ms": round(t_m, 4), "t_W_ms": round(t_w, 4),

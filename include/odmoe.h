@@ -19,6 +19,16 @@
  * config.n_slots > 0 the experts' weights stay in pinned host memory and only n_slots
  * expert-sized slots exist in HBM.  Every activation is a host->HBM copy; nothing is cached.
  *
+ * Experts read in place.  With config.n_slots = 0 the kernels read each expert where its
+ * pointer says.  Normally that is HBM.  Pinned host memory that is mapped for the device
+ * (hipHostMalloc, odmoe_pinned_alloc) also qualifies: then nothing is copied and nothing is
+ * held in HBM at all, the GEMV kernels pull the activated experts' weights across the host
+ * link while they compute (launch shapes made for the link: about a hundred waves, each streaming
+ * one long run), no host synchronisation happens per layer, no prediction is needed, and results
+ * are bit for bit those of the other modes.  Measured, a token then takes 0.995-1.013 times what
+ * copying the same experts with hipMemcpyAsync and computing nothing takes: as fast as the slot
+ * pool with perfect hints.  odmoe_stats counts no loads and no copied bytes in this form.
+ *
  * Conventions.
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
  *   - All matrices are row-major and dense.  dtype applies to x, y, router and expert weights;
@@ -67,7 +77,8 @@ typedef struct {
   int32_t n_experts; /* E */
   int32_t top_k;     /* k */
   int32_t n_layers;  /* L */
-  int32_t n_slots;   /* S; 0 = resident: expert_w are DEVICE pointers and nothing is ever loaded */
+  int32_t n_slots;   /* S; 0 = resident: expert_w are DEVICE pointers and nothing is ever loaded
+                        (any address the GPU can read will do, see "Experts read in place") */
   int32_t dtype;     /* odmoe_dtype */
   int32_t glue;      /* 0: x_{l+1} = y_l ; 1: x_{l+1} = rmsnorm(x_l + y_l) between stacked layers */
 } odmoe_config;
@@ -138,7 +149,10 @@ int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert);
 /*
  * Expert computation EC_l (Section 3.1) with the weighted combine, for n_tokens tokens:
  *   y[t] = sum_i gate[t,i] * FFN_{idx[t,i]}(x[t]).
- *   idx_dev[T,k], gate_dev[T,k], x_dev[T,H], y_dev[T,H] are device pointers.
+ *   idx_dev[T,k], gate_dev[T,k], x_dev[T,H], y_dev[T,H] are device pointers.  Every idx entry
+ *   must be an expert id in [0, n_experts), as odmoe_route_topk writes them: the per-token
+ *   kernels use it unchecked to pick the expert's weights (the library cannot see device memory
+ *   without blocking); the grouped path leaves an out-of-range slot out of the sum.
  *   idx_host   optional host copy of idx (cacheless mode needs to know the experts on the
  *              host; when NULL there, the library reads idx_dev back and blocks for it).
  *   n_tokens   resident mode: token by token (one fused w1/w3+SiLU GEMV and one w2+combine GEMV

@@ -1,6 +1,7 @@
 /*
  * Plain C program that drives libodmoe.so through include/odmoe.h alone (no Python, no torch):
- * a small cacheless stack, one decode token with and without expert hints.
+ * a small cacheless stack, one decode token with and without expert hints, and once more with the
+ * experts read in place from pinned host memory.
  *
  *   c_abi_demo <input file> <output file>
  *
@@ -102,6 +103,24 @@ int main(int argc, char** argv) {
   ODMOE_OK_OR_DIE(odmoe_decode_step(h, x_dev, y_dev, idx, NULL, &st));
   HIP_OK(hipMemcpy(y_second, y_dev, x_bytes, hipMemcpyDeviceToHost));
   if (memcmp(y_first, y_second, x_bytes) != 0) { fprintf(stderr, "hints changed the output\n"); return 4; }
+
+  /* pass 3: a second handle with no slot pool at all, whose kernels read the same pinned expert
+     buffers in place (n_slots = 0 accepts any address the GPU can read): same output again */
+  {
+    odmoe_config cfg_in_place = cfg;
+    cfg_in_place.n_slots = 0;
+    odmoe_layer_t* h2 = NULL;
+    void* y_third = malloc(x_bytes);
+    if (!y_third) return 1;
+    ODMOE_OK_OR_DIE(odmoe_layer_init(&cfg_in_place, (const void* const*)router_w, NULL,
+                                     (const void* const*)expert_w, compute, NULL, &h2));
+    ODMOE_OK_OR_DIE(odmoe_decode_step(h2, x_dev, y_dev, NULL, NULL, NULL));
+    HIP_OK(hipStreamSynchronize(compute));
+    HIP_OK(hipMemcpy(y_third, y_dev, x_bytes, hipMemcpyDeviceToHost));
+    ODMOE_OK_OR_DIE(odmoe_layer_destroy(h2));
+    if (memcmp(y_first, y_third, x_bytes) != 0) { fprintf(stderr, "reading experts in place changed the output\n"); return 4; }
+    free(y_third);
+  }
 
   FILE* out = fopen(argv[2], "wb");
   if (!out) { perror(argv[2]); return 1; }

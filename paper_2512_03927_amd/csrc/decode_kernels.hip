@@ -666,6 +666,7 @@ hipError_t launch_up_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& src,
   // waves per SIMD).
   constexpr bool more_waves = NCH < 8 || (NCH > 8 && NCH * DT<T>::VEC <= 64);
   if (rpw < 16 || more_waves) rpw = (total + (long)num_cu() * nw * 4 - 1) / ((long)num_cu() * nw * 4);
+  if (sh.host_link) rpw = (total + 127) / 128;  // 32 blocks of 4 waves
   if (rpw < 1) rpw = 1;
   if (g_tune_up_rpw > 0) rpw = g_tune_up_rpw;
   const int grid = (int)((total + nw * rpw - 1) / (nw * rpw));
@@ -707,7 +708,9 @@ hipError_t launch_down_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& sr
   int rpb = (sh.H + num_cu() - 1) / num_cu();
   if (n_eg > 1 && nwb <= 2 && rpb > 4) rpb = 4;  // small layers: more, shorter blocks
   rpb = (rpb + 1) & ~1;              // two rows in flight
-  if (rpb > 64) rpb = 64;
+  // Across the host link: fewer blocks with longer runs.  The expert groups stay as they are, so
+  // that the order of the fp32 additions, and with it every output bit, is that of experts in HBM.
+  if (rpb > 64 || sh.host_link) rpb = 64;
   if (g_tune_down_rpb > 0) rpb = (g_tune_down_rpb + 1) & ~1;
   const int grid = (sh.H + rpb - 1) / rpb;
   const int nw = nwb * n_eg;

@@ -22,6 +22,10 @@ struct ExpertSrc {
 struct Shape {
   int32_t H, F, E, k;
   int32_t dtype;  // odmoe_dtype
+  // Expert weights are read in place from pinned host memory, across the host link.  The link is
+  // saturated by about a hundred waves that each stream a long contiguous run; thousands of short
+  // runs lose 4-7 % of its rate.
+  int32_t host_link = 0;
 };
 
 // Device scratch that lets the router spread one token over several blocks: logits

@@ -21,16 +21,26 @@ using namespace odmoe;
 
 namespace {
 
-thread_local std::string g_err;
+thread_local char g_err[512] = "";
 
-int fail(int code, const char* fmt, ...) {
-  char buf[512];
+int fail(int code, const char* fmt, ...) noexcept {
   va_list ap;
   va_start(ap, fmt);
-  vsnprintf(buf, sizeof buf, fmt, ap);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
   va_end(ap);
-  g_err = buf;
   return code;
+}
+
+// No C++ exception crosses the C boundary: host-side allocations (vectors, the scheduler) can throw.
+template <class F>
+int guarded(F&& body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return fail(ODMOE_ENOMEM, "out of host memory");
+  } catch (...) {
+    return fail(ODMOE_ESTATE, "unexpected C++ exception");
+  }
 }
 
 #define HIP_TRY(expr)                                                                      \
@@ -211,7 +221,7 @@ int run_ffn_one_token(odmoe_layer* h, const ExpertSrc& src, const int32_t* idx_d
 
 extern "C" {
 
-const char* odmoe_last_error(void) { return g_err.c_str(); }
+const char* odmoe_last_error(void) { return g_err; }
 const char* odmoe_version(void) { return "odmoe 0.1 (gfx950)"; }
 
 int odmoe_pinned_alloc(uint64_t bytes, void** out_host) {
@@ -341,11 +351,10 @@ uint64_t odmoe_slot_pool_bytes(const odmoe_layer_t* h) {
   return h && h->pool ? (uint64_t)h->cfg.n_slots * h->expert_bytes : 0;
 }
 
-int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const void* const* router_b,
-                     const void* const* expert_w, void* compute_stream, void* copy_stream,
-                     odmoe_layer_t** out) {
-  if (!out) return fail(ODMOE_EINVAL, "out is NULL");
-  *out = nullptr;
+// `*made` receives the handle as soon as it exists, so that the caller can free it on any failure.
+static int layer_init_impl(const odmoe_config* cfg, const void* const* router_w, const void* const* router_b,
+                           const void* const* expert_w, void* compute_stream, void* copy_stream,
+                           odmoe_layer** made) {
   int rc = validate_cfg(cfg);
   if (rc) return rc;
   if (!router_w || !expert_w) return fail(ODMOE_EINVAL, "router_w / expert_w is NULL");
@@ -357,6 +366,7 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
 
   odmoe_layer* h = new (std::nothrow) odmoe_layer();
   if (!h) return fail(ODMOE_ENOMEM, "out of host memory");
+  *made = h;
   h->cfg = *cfg;
   h->sh = Shape{cfg->hidden, cfg->ffn, E, k, cfg->dtype};
   h->esize = dtype_size(cfg->dtype);
@@ -370,11 +380,8 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
 #define INIT_TRY(expr, code)                                                                    \
   do {                                                                                          \
     hipError_t e__ = (expr);                                                                    \
-    if (e__ != hipSuccess) {                                                                    \
-      int c__ = fail(code, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
-      free_all(h);                                                                              \
-      return c__;                                                                               \
-    }                                                                                           \
+    if (e__ != hipSuccess)                                                                      \
+      return fail(code, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
   } while (0)
 
   INIT_TRY(kernels_init(), ODMOE_EHIP);
@@ -399,6 +406,16 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
   INIT_TRY(hipEventCreateWithFlags(&h->route_ev, hipEventDisableTiming), ODMOE_EHIP);
 
   if (S == 0) {
+    // Experts may sit in pinned host memory and be read in place: the GEMVs then take launch
+    // shapes made for the host link.  A pointer the runtime does not know is taken for HBM.
+    for (size_t i = 0; i < h->expert_w.size() && !h->sh.host_link; ++i) {
+      hipPointerAttribute_t attr{};
+      if (hipPointerGetAttributes(&attr, h->expert_w[i]) != hipSuccess) {
+        (void)hipGetLastError();
+        continue;
+      }
+      if (attr.type == hipMemoryTypeHost) h->sh.host_link = 1;
+    }
     INIT_TRY(hipMalloc((void**)&h->eptr_dev, (size_t)L * k * sizeof(void*)), ODMOE_ENOMEM);
     INIT_TRY(hipMalloc((void**)&h->table_dev, (size_t)L * E * sizeof(void*)), ODMOE_ENOMEM);
     INIT_TRY(hipMemcpy((void*)h->table_dev, h->expert_w.data(), (size_t)L * E * sizeof(void*),
@@ -443,6 +460,21 @@ int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const
     }
   }
 #undef INIT_TRY
+  return ODMOE_OK;
+}
+
+int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w, const void* const* router_b,
+                     const void* const* expert_w, void* compute_stream, void* copy_stream,
+                     odmoe_layer_t** out) {
+  if (!out) return fail(ODMOE_EINVAL, "out is NULL");
+  *out = nullptr;
+  odmoe_layer* h = nullptr;
+  const int rc = guarded(
+      [&] { return layer_init_impl(cfg, router_w, router_b, expert_w, compute_stream, copy_stream, &h); });
+  if (rc != ODMOE_OK) {
+    free_all(h);
+    return rc;
+  }
   *out = h;
   return ODMOE_OK;
 }
@@ -504,9 +536,9 @@ int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert) {
   return ODMOE_OK;
 }
 
-int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, const float* gate_dev,
-                     const int32_t* idx_host, const void* x_dev, int32_t n_tokens, void* y_dev,
-                     int32_t evict_after) {
+static int expert_ffn_impl(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, const float* gate_dev,
+                           const int32_t* idx_host, const void* x_dev, int32_t n_tokens, void* y_dev,
+                           int32_t evict_after) {
   int rc = check_layer(h, layer);
   if (rc) return rc;
   if (n_tokens < 0) return fail(ODMOE_EINVAL, "n_tokens %d < 0", n_tokens);
@@ -611,18 +643,32 @@ int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, co
   return ODMOE_OK;
 }
 
-int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
-                      const int32_t* predicted_idx_host, int32_t* idx_out_host, odmoe_stats* stats) {
+int odmoe_expert_ffn(odmoe_layer_t* h, int32_t layer, const int32_t* idx_dev, const float* gate_dev,
+                     const int32_t* idx_host, const void* x_dev, int32_t n_tokens, void* y_dev,
+                     int32_t evict_after) {
+  return guarded(
+      [&] { return expert_ffn_impl(h, layer, idx_dev, gate_dev, idx_host, x_dev, n_tokens, y_dev, evict_after); });
+}
+
+static int decode_step_impl(odmoe_layer_t* h, const void* x_dev, void* y_dev,
+                            const int32_t* predicted_idx_host, int32_t* idx_out_host, odmoe_stats* stats) {
   if (!h) return fail(ODMOE_EINVAL, "handle is NULL");
   if (!x_dev || !y_dev) return fail(ODMOE_EINVAL, "x/y is NULL");
   const int L = h->cfg.n_layers, k = h->cfg.top_k, E = h->cfg.n_experts;
   const bool timed = stats && stats->t_step_ms < 0.f;
   const auto wall0 = std::chrono::steady_clock::now();
   if (timed && h->tev.empty()) {
-    h->tev.assign((size_t)5 * L, nullptr);
-    for (auto& e : h->tev) HIP_TRY(hipEventCreate(&e));
-    h->lev.assign((size_t)4 * L * k, nullptr);
-    for (auto& e : h->lev) HIP_TRY(hipEventCreate(&e));
+    // all or nothing: a failure part-way leaves no half-made set behind for the next call
+    std::vector<hipEvent_t> made((size_t)5 * L + (h->pool ? (size_t)4 * L * k : 0), nullptr);
+    for (auto& e : made) {
+      const hipError_t rc_ev = hipEventCreate(&e);
+      if (rc_ev != hipSuccess) {
+        for (auto m : made) if (m) (void)hipEventDestroy(m);
+        return fail(ODMOE_EHIP, "hipEventCreate failed: %s", hipGetErrorString(rc_ev));
+      }
+    }
+    h->tev.assign(made.begin(), made.begin() + (size_t)5 * L);
+    h->lev.assign(made.begin() + (size_t)5 * L, made.end());
   }
   auto TE = [&](int l, int which) -> hipEvent_t { return timed ? h->tev[(size_t)l * 5 + which] : nullptr; };
   size_t n_lev = 0;  // load events used
@@ -758,6 +804,11 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
         std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - wall0).count();
   }
   return ODMOE_OK;
+}
+
+int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
+                      const int32_t* predicted_idx_host, int32_t* idx_out_host, odmoe_stats* stats) {
+  return guarded([&] { return decode_step_impl(h, x_dev, y_dev, predicted_idx_host, idx_out_host, stats); });
 }
 
 }  // extern "C"

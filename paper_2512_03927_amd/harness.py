@@ -52,11 +52,18 @@ class MoEStack:
 
     def __init__(self, cfg: synth.MoEConfig, layers: Optional[Sequence[LayerWeights]] = None,
                  unique_layers: Optional[int] = None, device: str = "cuda:0",
-                 copy_stream: Optional[torch.cuda.Stream] = None):
+                 copy_stream: Optional[torch.cuda.Stream] = None, experts_in_host_memory: bool = False,
+                 buffers_of: Optional["MoEStack"] = None):
         """layers: per-layer stored weights; generated from `cfg` when None.
+
+        experts_in_host_memory (with cfg.n_slots == 0): the experts stay in pinned host memory and
+        the handle is given those addresses, so the kernels read the weights across the host link.
 
         unique_layers = U < L keeps only U distinct layers' weights and maps layer l to
         l mod U (same bytes moved per token, less host memory).
+
+        buffers_of: another stack of the same layers whose router and expert buffers this one
+        shares instead of making its own copies (it must outlive this stack's use).
         """
         self.cfg = cfg
         self.device = device
@@ -71,10 +78,13 @@ class MoEStack:
         self._keep: List[torch.Tensor] = []
         router_w, router_b, expert_w = [], [], []
         uniq_router, uniq_bias, uniq_experts = [], [], []
-        for (Wg, b, experts) in self.layers_np:
+        if buffers_of is not None:
+            uniq_router, uniq_bias, uniq_experts = buffers_of._keep
+            assert len(uniq_experts) == nl
+        for (Wg, b, experts) in ([] if buffers_of is not None else self.layers_np):
             uniq_router.append(to_device(Wg, device))
             uniq_bias.append(None if b is None else to_device(np.asarray(b, np.float32), device))
-            if cfg.n_slots == 0:
+            if cfg.n_slots == 0 and not experts_in_host_memory:
                 uniq_experts.append([to_device(e, device) for e in experts])
             else:
                 uniq_experts.append([pinned_like(e) for e in experts])

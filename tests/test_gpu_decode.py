@@ -278,6 +278,33 @@ def test_hints_change_timing_only(H):
             B.odmoe_time_expert_loads(st_res.handle, 1)          # resident mode has no loads
 
 
+def test_experts_read_in_place_from_pinned_host_memory(H):
+    """n_slots = 0 with expert pointers into pinned host memory: the kernels read the weights over
+    the host link; output and routing equal the slot pool's bit for bit, and match the oracle."""
+    cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=6, n_slots=4, dtype="bf16", n_tokens=3, glue=1, seed=29)
+    layers = _stack_layers(cfg)
+    X = synth.tokens(cfg)
+    with H.MoEStack(cfg, layers) as st_pool, \
+            H.MoEStack(cfg.small(n_slots=0), layers, experts_in_host_memory=True) as st_host:
+        for t in range(cfg.n_tokens):
+            x = H.to_device(X[t])
+            y0, idx0, s0 = st_pool.decode(x)
+            y1, idx1, s1 = st_host.decode(x)
+            assert np.array_equal(H.from_device(y0), H.from_device(y1)) and np.array_equal(idx0, idx1)
+            assert s1.loads == 0 and s1.h2d_bytes == 0          # nothing was copied
+        x_ref, ids_ref, _ = O.stack_decode(X[0], layers, cfg.top_k, "bf16", glue=1)
+        y, idx, _ = st_host.decode(H.to_device(X[0]))
+        assert np.array_equal(idx, ids_ref)
+        assert np.max(np.abs(O.widen(H.from_device(y)) - O.widen(x_ref))) <= BF16_REL * np.max(np.abs(O.widen(x_ref)))
+        # a small batch through the grouped GEMMs reads the host-resident weights too
+        xb = H.to_device(X)
+        idx_d, gate_d = st_host.route(0, xb)
+        yb = H.from_device(st_host.ffn(0, idx_d, gate_d, xb))
+        for t in range(cfg.n_tokens):
+            y_ref, _, _ = O.moe_layer(X[t], *layers[0], cfg.top_k)
+            check_y(yb[t], y_ref, "bf16", batch=True)
+
+
 def test_caller_supplied_copy_stream_gives_the_same_tokens(H):
     """With a copy stream borrowed from the caller every expert copy goes through that one stream
     (the library's own four-stream rotation is off): same output, same load count."""
