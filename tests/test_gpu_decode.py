@@ -84,6 +84,8 @@ SHAPES = [
     (256, 8192, 4, 2, "bf16"),      # w2 rows of 16 chunks: four column slices x two expert groups per block
     (4096, 256, 4, 2, "f32"),       # fp32 rows of 16 register chunks (16 waves per CU in the w1/w3 GEMV)
     (6144, 64, 4, 2, "bf16"),       # bf16 rows of 12 register chunks
+    (40960, 8, 2, 1, "f32"),        # the longest hidden vector the library takes (160 KB of LDS in the fallback)
+    (8, 40960, 3, 2, "bf16"),       # the longest ffn vector
 ]
 
 
