@@ -261,7 +261,7 @@ def main() -> int:
         xs = [harness.to_device(r) for r in x_rows]
         yc = torch.empty_like(xs[0])
         s = B.odmoe_stats()
-        for _ in range(2):                                               # warm-up tokens
+        for _ in range(min(8, max(2, n_tok // 3))):                       # warm-up tokens (not timed)
             B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)
         torch.cuda.synchronize()
         yc_first = yc.clone()
