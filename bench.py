@@ -240,16 +240,34 @@ def main() -> int:
             torch.cuda.synchronize()
             el32 = time.perf_counter() - t1
             r_us, u_us, d_us = B.odmoe_time_decode_kernels(st32.handle, 0, X32, args.fp32_tokens, 2)
-            y0 = harness.from_device(Y32[0])
-        from oracle import moe_oracle as O32
-        y_ref, _, _ = O32.moe_layer(X32_np[0], layer32[0], layer32[1], layer32[2], c32.top_k)
+            # prefill of 512 tokens in fp32: grouped GEMMs on the fp32 matrix instructions
+            pf32 = None
+            if args.prefill_iters > 0:
+                Tp = 512
+                Xp_np = synth.tokens(c32, Tp)
+                Xp = harness.to_device(Xp_np)
+                idx_p, gate_p = st32.route(0, Xp)
+                Yp = torch.empty_like(Xp)
+                B.odmoe_expert_ffn(st32.handle, 0, idx_p, gate_p, None, Xp, Tp, Yp, 0)
+                torch.cuda.synchronize()
+                tp = []
+                for _ in range(args.prefill_iters):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    B.odmoe_expert_ffn(st32.handle, 0, idx_p, gate_p, None, Xp, Tp, Yp, 0)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    tp.append(e0.elapsed_time(e1))
+                ms_p = float(np.median(tp))
+                flop_p = 6.0 * c32.hidden * c32.ffn * Tp * c32.top_k
+                pf32 = {"tokens": Tp, "ms": round(ms_p, 3), "TFLOPs": round(flop_p / ms_p / 1e9, 1),
+                        "frac_of_fp32_matrix_peak_157.3": round(flop_p / ms_p / 1e9 / 157.3, 3)}
         ub32 = c32.top_k * 2 * c32.hidden * c32.ffn * 4
         fp32 = {"workload": c32.name, "tokens": args.fp32_tokens,
                 "tokens_per_s": round(args.fp32_tokens / el32, 1),
                 "ffn_up_us": round(u_us, 2), "ffn_up_GBps": round(ub32 / u_us / 1e3, 1),
                 "ffn_down_us": round(d_us, 2), "ffn_down_GBps": round(ub32 / 2 / d_us / 1e3, 1),
-                "route_us": round(r_us, 2),
-                "token0_max_abs_err_vs_oracle": float(np.max(np.abs(y0.astype(np.float64) - y_ref)))}
+                "route_us": round(r_us, 2), "prefill": pf32}
         del layer32
         log(f"[bench] fp32: {fp32}")
 

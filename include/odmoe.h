@@ -160,15 +160,17 @@ int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert);
  *              host; when NULL there, the library reads idx_dev back and blocks for it).
  *   n_tokens   resident mode: token by token (one fused w1/w3+SiLU GEMV and one w2+combine GEMV
  *              per token) while the token-slots do not outnumber the experts
- *              (n_tokens * top_k <= n_experts and n_tokens < 16); larger batches (bf16, hidden and
+ *              (n_tokens * top_k <= n_experts and n_tokens < 16); larger batches (hidden and
  *              ffn multiples of 64) take the prefill path of Section 3.3 -- tokens are grouped by
  *              expert and each expert runs a grouped GEMM on the matrix cores, reading its
- *              weights once; the SwiGLU intermediate is rounded to bf16 there (the matrix cores
- *              take bf16 operands).  Other shapes stay on the per-token path.
+ *              weights once; in bf16 layers the SwiGLU intermediate is rounded to bf16 there (the
+ *              matrix cores take bf16 operands), fp32 layers (the paper's full precision) use the
+ *              fp32 matrix instructions and round nothing.  Other shapes stay on the per-token
+ *              path.
  *   evict_after  cacheless mode: nonzero releases the experts' slots after the kernels that
  *              read them (the paper's prompt eviction).  Ignored in resident mode.
  * Cacheless mode: n_tokens == 1 needs every chosen expert loading or ready (ESTATE otherwise);
- * the compute stream waits (stream side) for each copy.  n_tokens >= 2 (bf16, hidden and ffn
+ * the compute stream waits (stream side) for each copy.  n_tokens >= 2 (hidden and ffn
  * multiples of 64; EINVAL otherwise) is the prefill of Section 3.3 from host memory: the call
  * itself streams every expert that received tokens into a slot exactly once (experts already
  * loading or ready are used as they are), runs that expert's grouped GEMMs when its copy has

@@ -573,7 +573,7 @@ static int expert_ffn_impl(odmoe_layer_t* h, int32_t layer, const int32_t* idx_d
   // the next expert overlaps the GEMMs of the current one.
   if (n_tokens >= 2) {
     if (!prefill_supported(h->sh))
-      return fail(ODMOE_EINVAL, "cacheless batches need bf16 and hidden/ffn multiples of 64");
+      return fail(ODMOE_EINVAL, "cacheless batches need hidden and ffn to be multiples of 64");
     if ((rc = ensure_prefill_ws(h, n_tokens))) return rc;
     const size_t n = (size_t)n_tokens * k;
     std::vector<int32_t> ids_all(n);

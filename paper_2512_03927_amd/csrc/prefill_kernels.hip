@@ -1,10 +1,11 @@
 // Prefill path (paper Section 3.3): all experts of the layer are available, token embeddings
 // are grouped by the expert they were routed to, and each expert runs one larger matrix
 // multiplication.  On gfx950 that multiplication goes to the matrix cores
-// (v_mfma_f32_32x32x16_bf16); everything else here is bookkeeping around it:
+// (v_mfma_f32_32x32x16_bf16 for bf16 layers, v_mfma_f32_32x32x2_f32 for fp32 layers, the paper's
+// full precision); everything else here is bookkeeping around it:
 //
 //   sort      token-slots (t, i) bucketed by expert -> offsets[E+1], perm, inv, list of M-tiles
-//   gemm1     Hbuf[p, :] = silu(X[tok(p)] W1_e^T) * (X[tok(p)] W3_e^T)       bf16 [T*k, F]
+//   gemm1     Hbuf[p, :] = silu(X[tok(p)] W1_e^T) * (X[tok(p)] W3_e^T)       dtype [T*k, F]
 //   gemm2     Ybuf[p, :] = Hbuf[p, :] W2_e^T                                  fp32 [T*k, H]
 //   combine   Y[t] = sum_i gate[t,i] * Ybuf[inv[t*k+i]]                       (fixed order, no atomics)
 //
@@ -12,13 +13,14 @@
 // which is exactly how the MFMA operands want to be fed (8 consecutive K elements per lane).
 #include "kernels.h"
 
+#include <type_traits>
+
 namespace odmoe {
 namespace {
 
 constexpr int BMX = 256;     // most rows of one expert a block takes (one "chunk")
 constexpr int BN = 256;      // weight rows per block tile: two 128-row halves (W1 and W3 rows of the
                              // same 128 ffn columns for the first GEMM, 256 consecutive rows for the second)
-constexpr int BK = 64;       // K elements per pipeline step (one 128-byte line per row)
 constexpr int GEMM_THREADS = 512;
 constexpr int MAX_KSPLIT = 8;
 constexpr int TILE_REC = 5;   // ints per entry of the chunk list
@@ -29,6 +31,20 @@ typedef uint16_t bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Element types of the grouped GEMM.  A pipeline step is one 128-byte line per row whatever the
+// type; a 16-byte piece of it (what one lane fetches and what one lane reads back as an MFMA
+// fragment) holds PIECE elements.
+template <typename E>
+struct ElemT;
+template <>
+struct ElemT<uint16_t> {
+  static constexpr int PIECE = 8, BKE = 64;
+};
+template <>
+struct ElemT<float> {
+  static constexpr int PIECE = 4, BKE = 32;
+};
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
 
@@ -122,8 +138,8 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //     exactly once; the chunks of a larger expert are started together on one XCD (see the block
 //     order in grouped_gemm_kernel) so that the second one finds the weight tile in L2;
 //   - global memory goes straight into LDS (global_load_lds_dwordx4: a wave fills 1 KB = 8 rows of
-//     128 bytes per instruction, every 128-byte line fully coalesced) in a ring of K-steps of
-//     BK = 64; no staging registers, one s_barrier per step, and the only vmcnt wait is for the
+//     128 bytes per instruction, every 128-byte line fully coalesced) in a ring of K-steps of one
+//     128-byte line per row (64 bf16 or 32 fp32 elements); no staging registers, one s_barrier per step, and the only vmcnt wait is for the
 //     step about to be used.  The ring holds 3 steps of 40 / 48 KB for up to 64 / 128 rows and 2
 //     steps of 56 / 64 KB for up to 192 / 256 rows (measured: deeper rings do not help: the CU's
 //     vector L1 keeps only about 125 128-byte requests in flight whatever is queued behind them);
@@ -144,7 +160,10 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //           ksplit, [gridDim.z][rows, ldo]
 // K is a multiple of 64.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ int lds_slot(int row, int piece) { return row * BK + ((piece ^ (row & 7)) << 3); }
+template <typename E>
+__device__ __forceinline__ int lds_slot(int row, int piece) {
+  return row * ElemT<E>::BKE + (piece ^ (row & 7)) * ElemT<E>::PIECE;
+}
 
 // s_waitcnt vmcnt(N) only (other counters left at their maximum).
 #define ODMOE_VMCNT(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
@@ -153,7 +172,7 @@ typedef const __attribute__((address_space(1))) void* global_void_ptr;
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 
 struct GemmArgs {
-  const bf16_t* A;            // activations [rows, lda]
+  const void* A;              // activations [rows, lda]
   int lda;
   const int32_t* a_slot;      // sorted position -> token-slot (row of A = slot / slot_div), or null
   int slot_div;
@@ -171,17 +190,18 @@ struct GemmArgs {
   size_t split_stride;
 };
 
-template <bool SILU, int NT, int NSTAGE>
-__device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int ntile, int ksplit, int e, int row_lo, int nrows) {
+template <typename E, bool SILU, int NT, int NSTAGE>
+__device__ __forceinline__ void gemm_chunk(const GemmArgs& g, E* smem, int ntile, int ksplit, int e, int row_lo, int nrows) {
+  constexpr int BKE = ElemT<E>::BKE, PIECE = ElemT<E>::PIECE;
   constexpr int A_INSTR = (NT + 1) / 2;                 // A fills per wave per K-step (64 rows each)
   constexpr int A_ROWS = 64 * A_INSTR;                  // rows of activations staged (NT 32-row tiles used)
   constexpr int MTW = (NT + 1) / 2;                     // 32-row tiles per wave: tiles wm, wm+2, wm+4, ...
   constexpr int B_INSTR = BN / 64;                      // B fills per wave per K-step
   constexpr int LPS = A_INSTR + B_INSTR;                // DMA loads per wave per K-step
   constexpr bool ODD_NT = (NT & 1) != 0;                // the last 64-row group is half used
-  constexpr size_t A_STAGE = (size_t)A_ROWS * BK;
-  constexpr size_t STAGE = A_STAGE + (size_t)BN * BK;
-  static_assert(NSTAGE * STAGE * sizeof(bf16_t) <= GEMM_LDS, "ring does not fit");
+  constexpr size_t A_STAGE = (size_t)A_ROWS * BKE;
+  constexpr size_t STAGE = A_STAGE + (size_t)BN * BKE;
+  static_assert(NSTAGE * STAGE * sizeof(E) <= GEMM_LDS, "ring does not fit");
   static_assert((NSTAGE - 2) * LPS < 64, "vmcnt is 6 bits");
 
   const int n0 = ntile * (SILU ? BN / 2 : BN);
@@ -193,30 +213,30 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   const int k_begin = ksplit * g.k_per_split;
   const int k_end = (k_begin + g.k_per_split < K) ? k_begin + g.k_per_split : K;
   if (k_begin >= k_end) return;
-  const int nk = (k_end - k_begin) / BK;
+  const int nk = (k_end - k_begin) / BKE;
 
   // ---- what this lane fetches: row (lane >> 3) of each 8-row group, piece (lane & 7) ^ (lane >> 3)
   const int sub = lane >> 3;
   const int piece = (lane & 7) ^ sub;
-  const bf16_t* a_src[A_INSTR];
+  const E* a_src[A_INSTR];
 #pragma unroll
   for (int i = 0; i < A_INSTR; ++i) {
     int r = (i * 8 + wave) * 8 + sub;
     r = r < nrows ? r : nrows - 1;                      // rows past the chunk: repeat its last row
     const int p = row_lo + r;
     const int src_row = g.a_slot ? g.a_slot[p] / g.slot_div : p;
-    a_src[i] = g.A + (size_t)src_row * g.lda + k_begin + piece * 8;
+    a_src[i] = static_cast<const E*>(g.A) + (size_t)src_row * g.lda + k_begin + piece * PIECE;
   }
-  const bf16_t* wbase =
-      static_cast<const bf16_t*>(g.expert_override ? g.expert_override : g.table[g.table_off + e]);
-  const bf16_t* b_src[B_INSTR];                         // LDS rows (i*8 + wave)*8 + sub of the B tile
+  const E* wbase =
+      static_cast<const E*>(g.expert_override ? g.expert_override : g.table[g.table_off + e]);
+  const E* b_src[B_INSTR];                         // LDS rows (i*8 + wave)*8 + sub of the B tile
 #pragma unroll
   for (int i = 0; i < B_INSTR; ++i) {
     const int br = (i * 8 + wave) * 8 + sub;            // 0..255: half = br / 128, row in half = br % 128
     const int half = br >> 7;
     int n = n0 + g.b_row[half] + (br & 127);
     n = n < g.N ? n : g.N - 1;                          // rows past N: any valid row (never stored)
-    b_src[i] = wbase + g.b_off[half] + (size_t)n * K + k_begin + piece * 8;
+    b_src[i] = wbase + g.b_off[half] + (size_t)n * K + k_begin + piece * PIECE;
   }
   // Blocks that run side by side start their K loops at different steps: rows of a row-major
   // matrix lie a multiple of 4 KB apart, so blocks marching through K in lockstep would keep
@@ -225,24 +245,24 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   auto step_offset = [&](int kt) {
     int kr = kt + kt0;
     kr = kr >= nk ? kr - nk : kr;
-    return kr * BK;
+    return kr * BKE;
   };
   auto issue_a = [&](int stage, int kt) {
-    bf16_t* sa = smem + stage * STAGE;
+    E* sa = smem + stage * STAGE;
     const int ko = step_offset(kt);
 #pragma unroll
     for (int i = 0; i < A_INSTR; ++i)
       if (i + 1 < A_INSTR || !ODD_NT || wave < 4)   // odd tile count: the last fill covers 32 rows only
         __builtin_amdgcn_global_load_lds((global_void_ptr)(a_src[i] + ko),
-                                         (lds_void_ptr)(sa + (i * 8 + wave) * 8 * BK), 16, 0, 0);
+                                         (lds_void_ptr)(sa + (i * 8 + wave) * 8 * BKE), 16, 0, 0);
   };
   auto issue_b = [&](int stage, int kt) {
-    bf16_t* sa = smem + stage * STAGE;
+    E* sa = smem + stage * STAGE;
     const int ko = step_offset(kt);
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i)
       __builtin_amdgcn_global_load_lds((global_void_ptr)(b_src[i] + ko),
-                                       (lds_void_ptr)(sa + A_STAGE + (i * 8 + wave) * 8 * BK), 16, 0, 0);
+                                       (lds_void_ptr)(sa + A_STAGE + (i * 8 + wave) * 8 * BKE), 16, 0, 0);
   };
   // With a two-deep ring only one step is in flight: the weight fills (HBM) go out first and the
   // activation fills (L2 hits) half a step later, which spreads the requests over the step.
@@ -277,25 +297,37 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
     if (!SPLIT_ISSUE) issue_a(refill, nxt);            // refill the buffer that step kt-1 used
     issue_b(refill, nxt);
     {
-      const bf16_t* sa = smem + stage * STAGE;
-      const bf16_t* sb = sa + A_STAGE;
+      const E* sa = smem + stage * STAGE;
+      const E* sb = sa + A_STAGE;
+      // The 128-byte line of a row is 8 pieces of 16 bytes; lane group fg takes pieces fg, 2+fg, ...
+      // bf16: a piece is the 8 consecutive K elements of one 32x32x16 MFMA operand.  fp32: a piece is
+      // 4 consecutive K elements; MFMA j of a piece multiplies element j of the pieces of both lane
+      // groups (K indices 8s+j and 8s+4+j), the same pairing for activations and weights.
+      typedef typename std::conditional<sizeof(E) == 2, bf16x8, f32x4>::type frag_t;
 #pragma unroll
-      for (int s = 0; s < BK / 16; ++s) {
+      for (int s = 0; s < 4; ++s) {
         const int pc = 2 * s + fg;
-        if (SPLIT_ISSUE && s == BK / 32) issue_a(refill, nxt);
-        bf16x8 bfrag[2], afrag[MTW];
+        if (SPLIT_ISSUE && s == 2) issue_a(refill, nxt);
+        frag_t bfrag[2], afrag[MTW];
 #pragma unroll
         for (int b = 0; b < 2; ++b)
-          bfrag[b] = *reinterpret_cast<const bf16x8*>(sb + lds_slot(b * 128 + wn * 32 + fr, pc));
+          bfrag[b] = *reinterpret_cast<const frag_t*>(sb + lds_slot<E>(b * 128 + wn * 32 + fr, pc));
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt)
-          if (tile_on(mt)) afrag[mt] = *reinterpret_cast<const bf16x8*>(sa + lds_slot((2 * mt + wm) * 32 + fr, pc));
+          if (tile_on(mt)) afrag[mt] = *reinterpret_cast<const frag_t*>(sa + lds_slot<E>((2 * mt + wm) * 32 + fr, pc));
 #pragma unroll
         for (int mt = 0; mt < MTW; ++mt)
           if (tile_on(mt)) {
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-              acc[mt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mt], bfrag[b], acc[mt][b], 0, 0, 0);
+            for (int b = 0; b < 2; ++b) {
+              if constexpr (sizeof(E) == 2) {
+                acc[mt][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mt], bfrag[b], acc[mt][b], 0, 0, 0);
+              } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                  acc[mt][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(afrag[mt][j], bfrag[b][j], acc[mt][b], 0, 0, 0);
+              }
+            }
           }
       }
     }
@@ -317,8 +349,9 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
           const int col = n0 + wn * 32 + fr;
           if (col < g.N) {
             const float a = acc[mt][0][i], b = acc[mt][1][i];
-            ((__attribute__((address_space(1))) bf16_t*)g.out)[p * g.ldo + col] =
-                f32_to_bf16(a / (1.f + expf(-a)) * b);
+            const float hval = a / (1.f + expf(-a)) * b;
+            if constexpr (sizeof(E) == 2) ((__attribute__((address_space(1))) bf16_t*)g.out)[p * g.ldo + col] = f32_to_bf16(hval);
+            else ((__attribute__((address_space(1))) float*)g.out)[p * g.ldo + col] = hval;
           }
         } else {
 #pragma unroll
@@ -334,9 +367,10 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, bf16_t* smem, int 
   }
 }
 
-template <bool SILU>
+template <typename E, bool SILU>
 __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  E* smem = reinterpret_cast<E*>(smem_raw);
   // Blocks are dispatched in the order x + gridDim.x * (y + gridDim.y * z), round-robin over the
   // 8 XCDs.  That order is re-read as [y][x][K split]: with 8 K splits every XCD works on one K
   // range, so the blocks that read the same activation columns (all N tiles of a chunk) and the
@@ -359,24 +393,25 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) 
   const int row_lo = g.offsets[e] + g.tiles[TILE_REC * tile + 1];
   const int nrows = g.tiles[TILE_REC * tile + 2];
   switch ((nrows + 31) >> 5) {      // 32-row tiles of the chunk
-    case 1: gemm_chunk<SILU, 1, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    case 2: gemm_chunk<SILU, 2, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    case 3: gemm_chunk<SILU, 3, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    case 4: gemm_chunk<SILU, 4, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    case 5: gemm_chunk<SILU, 5, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    case 6: gemm_chunk<SILU, 6, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    case 7: gemm_chunk<SILU, 7, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    default: gemm_chunk<SILU, 8, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 1: gemm_chunk<E, SILU, 1, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 2: gemm_chunk<E, SILU, 2, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 3: gemm_chunk<E, SILU, 3, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 4: gemm_chunk<E, SILU, 4, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 5: gemm_chunk<E, SILU, 5, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 6: gemm_chunk<E, SILU, 6, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 7: gemm_chunk<E, SILU, 7, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    default: gemm_chunk<E, SILU, 8, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
   }
 }
 
-// Y[t, :] = sum_i gate[t,i] * (sum_z Ybuf[z][inv[t*k+i], :]), rounded once to bf16.  Block (t, j)
+// Y[t, :] = sum_i gate[t,i] * (sum_z Ybuf[z][inv[t*k+i], :]), rounded once to the layer's dtype.  Block (t, j)
 // takes columns j*1024 .. j*1024+1023 of token t, four per thread; the partial sums of one slot are
 // fetched together (independent loads) and added in a fixed order (z inner, i outer).
+template <typename E>
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ ybuf,
                                                        const int32_t* __restrict__ inv,
                                                        const float* __restrict__ gate,
-                                                       bf16_t* __restrict__ Y, int H, int k, int n_split,
+                                                       E* __restrict__ Y, int H, int k, int n_split,
                                                        size_t split_stride) {
   const int t = blockIdx.x;
   const int c = (blockIdx.y * 256 + threadIdx.x) * 4;
@@ -398,16 +433,20 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
     acc.x = fmaf(g, v.x, acc.x); acc.y = fmaf(g, v.y, acc.y);
     acc.z = fmaf(g, v.z, acc.z); acc.w = fmaf(g, v.w, acc.w);
   }
-  const uint32_t lo = (uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16);
-  const uint32_t hi = (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16);
-  *reinterpret_cast<uint2*>(Y + (size_t)t * H + c) = make_uint2(lo, hi);
+  if constexpr (sizeof(E) == 2) {
+    const uint32_t lo = (uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16);
+    const uint32_t hi = (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16);
+    *reinterpret_cast<uint2*>(Y + (size_t)t * H + c) = make_uint2(lo, hi);
+  } else {
+    *reinterpret_cast<f32x4*>(Y + (size_t)t * H + c) = acc;
+  }
 }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Carve {
   int32_t *offsets, *perm, *inv, *tiles, *n_tiles;
-  bf16_t* hbuf;
+  void* hbuf;
   float* ybuf;
   size_t total;
 };
@@ -426,7 +465,7 @@ Carve carve(const Shape& sh, int32_t T, void* base) {
   c.inv = reinterpret_cast<int32_t*>(take(n * sizeof(int32_t)));
   c.tiles = reinterpret_cast<int32_t*>(take(TILE_REC * max_tiles * sizeof(int32_t)));
   c.n_tiles = reinterpret_cast<int32_t*>(take(sizeof(int32_t)));
-  c.hbuf = reinterpret_cast<bf16_t*>(take(n * sh.F * sizeof(bf16_t)));
+  c.hbuf = take(n * sh.F * (sh.dtype == ODMOE_F32 ? sizeof(float) : sizeof(bf16_t)));
   int n_split = 1, k_per_split = 0;
   w2_split(sh, T, &n_split, &k_per_split);
   c.ybuf = reinterpret_cast<float*>(take((size_t)n_split * n * sh.H * sizeof(float)));
@@ -437,7 +476,7 @@ Carve carve(const Shape& sh, int32_t T, void* base) {
 }  // namespace
 
 bool prefill_supported(const Shape& sh) {
-  return sh.dtype == ODMOE_BF16 && sh.H % 64 == 0 && sh.F % 64 == 0;
+  return (sh.dtype == ODMOE_BF16 || sh.dtype == ODMOE_F32) && sh.H % 64 == 0 && sh.F % 64 == 0;
 }
 
 size_t prefill_workspace_bytes(const Shape& sh, int32_t T) { return carve(sh, T, nullptr).total; }
@@ -461,12 +500,14 @@ namespace {
 hipError_t ensure_attrs() {
   static bool attr_set = false;
   if (attr_set) return hipSuccess;
-  hipError_t ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<true>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
-  if (ea != hipSuccess) return ea;
-  ea = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gemm_kernel<false>),
-                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
-  if (ea != hipSuccess) return ea;
+  const void* kernels[4] = {reinterpret_cast<const void*>(grouped_gemm_kernel<bf16_t, true>),
+                            reinterpret_cast<const void*>(grouped_gemm_kernel<bf16_t, false>),
+                            reinterpret_cast<const void*>(grouped_gemm_kernel<float, true>),
+                            reinterpret_cast<const void*>(grouped_gemm_kernel<float, false>)};
+  for (const void* fn : kernels) {
+    const hipError_t ea = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)GEMM_LDS);
+    if (ea != hipSuccess) return ea;
+  }
   attr_set = true;
   return hipSuccess;
 }
@@ -477,14 +518,15 @@ hipError_t ensure_attrs() {
 // per block).  A function of the shape and the token count only: the GEMM and the combine agree.
 void w2_split(const Shape& sh, int32_t T, int* n_split, int* k_per_split) {
   const int nt2 = (sh.H + BN - 1) / BN;
-  const int ksteps = sh.F / BK;
+  const int bk = sh.dtype == ODMOE_F32 ? ElemT<float>::BKE : ElemT<bf16_t>::BKE;
+  const int ksteps = sh.F / bk;
   const long slots = (long)T * sh.k;
   const long chunks = slots < sh.E ? slots : sh.E;
   long ns = (2 * 256 + nt2 * chunks - 1) / (nt2 * chunks);
   if (ns > MAX_KSPLIT) ns = MAX_KSPLIT;
   if (ns > ksteps / 8) ns = ksteps / 8;
   if (ns < 1) ns = 1;
-  *k_per_split = (int)((ksteps + ns - 1) / ns) * BK;
+  *k_per_split = (int)((ksteps + ns - 1) / ns) * bk;
   *n_split = (sh.F + *k_per_split - 1) / *k_per_split;
 }
 
@@ -511,7 +553,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   const size_t hf = (size_t)sh.H * sh.F;
 
   GemmArgs g1{};
-  g1.A = static_cast<const bf16_t*>(x); g1.lda = sh.H; g1.a_slot = c.perm; g1.slot_div = sh.k;
+  g1.A = x; g1.lda = sh.H; g1.a_slot = c.perm; g1.slot_div = sh.k;
   g1.table = table; g1.table_off = table_off; g1.expert_override = expert_override; g1.tile_first = tile_first;
   g1.b_off[0] = 0; g1.b_off[1] = hf; g1.b_row[0] = 0; g1.b_row[1] = 0;        // W1 and W3 rows n0..n0+127
   g1.offsets = c.offsets; g1.tiles = c.tiles; g1.n_tiles = c.n_tiles;
@@ -520,7 +562,8 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   // share an N tile land on the same XCD and its L2), y = chunk, z = K split.
   auto pad8 = [](int v) { return (v + 7) & ~7; };
   dim3 grid1(pad8((sh.F + BN / 2 - 1) / (BN / 2)), tile_count, 1);
-  grouped_gemm_kernel<true><<<grid1, GEMM_THREADS, GEMM_LDS, s>>>(g1);
+  if (sh.dtype == ODMOE_F32) grouped_gemm_kernel<float, true><<<grid1, GEMM_THREADS, GEMM_LDS, s>>>(g1);
+  else grouped_gemm_kernel<bf16_t, true><<<grid1, GEMM_THREADS, GEMM_LDS, s>>>(g1);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
@@ -534,7 +577,8 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   g2.out = c.ybuf; g2.ldo = sh.H; g2.N = sh.H; g2.K = sh.F; g2.k_per_split = k_per_split;
   g2.split_stride = (size_t)n * sh.H;
   dim3 grid2(pad8((sh.H + BN - 1) / BN), tile_count, n_split);
-  grouped_gemm_kernel<false><<<grid2, GEMM_THREADS, GEMM_LDS, s>>>(g2);
+  if (sh.dtype == ODMOE_F32) grouped_gemm_kernel<float, false><<<grid2, GEMM_THREADS, GEMM_LDS, s>>>(g2);
+  else grouped_gemm_kernel<bf16_t, false><<<grid2, GEMM_THREADS, GEMM_LDS, s>>>(g2);
   return hipGetLastError();
 }
 
@@ -543,8 +587,12 @@ hipError_t prefill_combine(hipStream_t s, const Shape& sh, const float* gate, in
   const Carve c = carve(sh, T, workspace);
   int n_split, k_per_split;
   w2_split(sh, T, &n_split, &k_per_split);
-  combine_kernel<<<dim3(T, (sh.H + 1023) / 1024), 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split,
-                                   (size_t)T * sh.k * sh.H);
+  const dim3 grid(T, (sh.H + 1023) / 1024);
+  const size_t stride = (size_t)T * sh.k * sh.H;
+  if (sh.dtype == ODMOE_F32)
+    combine_kernel<float><<<grid, 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<float*>(y), sh.H, sh.k, n_split, stride);
+  else
+    combine_kernel<bf16_t><<<grid, 256, 0, s>>>(c.ybuf, c.inv, gate, static_cast<bf16_t*>(y), sh.H, sh.k, n_split, stride);
   return hipGetLastError();
 }
 

@@ -1,8 +1,9 @@
 """GPU parity of the prefill path (tokens grouped by expert, grouped GEMM on the matrix cores)
 against the CPU oracle, which simply applies the layer definition to every token.
 
-Tolerance: bf16, max-abs-err <= 2e-2 * max|y_ref| per token (the benchmark's bound).  The
-prefill kernels round the SwiGLU intermediate to bf16 before the w2 GEMM; the oracle does not.
+Tolerance: bf16, max-abs-err <= 2e-2 * max|y_ref| per token (the benchmark's bound); the bf16
+prefill kernels round the SwiGLU intermediate to bf16 before the w2 GEMM, the oracle does not.
+fp32 layers: max-abs-err <= 1e-4.
 """
 import numpy as np
 import pytest
@@ -71,7 +72,7 @@ def test_prefill_unsupported_shape_falls_back_to_per_token_path(H):
         x = H.to_device(X)
         idx, gate = st.route(0, x)
         _check_tokens(H.from_device(st.ffn(0, idx, gate, x)), Y, range(cfg.n_tokens))
-    cfg32 = synth.MoEConfig("t", 128, 128, 4, 2, dtype="f32", n_tokens=18, seed=23)   # fp32: no matrix-core path
+    cfg32 = synth.MoEConfig("t", 136, 136, 4, 2, dtype="f32", n_tokens=18, seed=23)   # fp32, not multiples of 64
     Wg, b, experts = synth.layer_weights(cfg32)
     X = synth.tokens(cfg32)
     Y, _, _ = O.moe_layer_tokens(X, Wg, b, experts, 2)
@@ -79,6 +80,45 @@ def test_prefill_unsupported_shape_falls_back_to_per_token_path(H):
         x = H.to_device(X)
         idx, gate = st.route(0, x)
         yn = H.from_device(st.ffn(0, idx, gate, x))
+        assert np.max(np.abs(yn - Y)) <= 1e-4
+
+
+@pytest.mark.parametrize("Hd,F,E,k,T,bias", [
+    (256, 512, 4, 2, 600, True),     # chunks of up to 256 rows, ragged tails, skewed routing
+    (128, 192, 8, 3, 257, True),     # k = 3, odd token count, K split of the w2 GEMM
+    (512, 1024, 8, 2, 16, False),    # config 1's layer shape, smallest batch on the grouped path
+    (64, 64, 16, 4, 1500, False),    # one K step per block, about 30 chunks
+])
+def test_fp32_prefill_matches_oracle(H, Hd, F, E, k, T, bias):
+    """Full-precision layers take the grouped GEMMs too (fp32 matrix instructions, nothing rounded
+    on the way): parity to the fp32 bound, and equal to the per-token GEMV path within it."""
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype="f32", n_tokens=T, router_bias=bias, seed=31)
+    Wg, b, experts = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Y, IDX, G = O.moe_layer_tokens(X, Wg, b, experts, k)
+    with H.MoEStack(cfg, [(Wg, b, experts)]) as st:
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        assert np.array_equal(idx.cpu().numpy(), IDX)
+        yn = H.from_device(st.ffn(0, idx, gate, x))
+        assert yn.dtype == np.float32
+        assert np.max(np.abs(yn - Y)) <= 1e-4
+        y1 = H.from_device(st.ffn(0, idx[:1].contiguous(), gate[:1].contiguous(), x[:1].contiguous()))   # GEMV path
+        assert np.max(np.abs(y1[0] - yn[0])) <= 1e-4
+        y_again = H.from_device(st.ffn(0, idx, gate, x))
+        assert np.array_equal(y_again, yn)
+
+
+def test_fp32_cacheless_prefill_from_host(H):
+    """fp32 batches in cacheless mode stream each expert once, like bf16 ones."""
+    cfg = synth.MoEConfig("t", 128, 256, 8, 2, n_layers=1, n_slots=3, dtype="f32", n_tokens=200, seed=33)
+    Wg, b, experts = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Y, IDX, _ = O.moe_layer_tokens(X, Wg, b, experts, cfg.top_k)
+    with H.MoEStack(cfg, [(Wg, b, experts)]) as st:
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        yn = H.from_device(st.ffn(0, idx, gate, x, idx_host=np.ascontiguousarray(IDX)))
         assert np.max(np.abs(yn - Y)) <= 1e-4
 
 
