@@ -58,7 +58,7 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 // Bucket the n = T*k token-slots by expert.  One block.  Slots with an out-of-range expert id
 // are left out (inv = -1) and contribute nothing.
 // tiles: one record of TILE_REC ints per chunk: expert, first row within the expert, rows (at most
-// BMX, the rows of an expert split evenly over its chunks), index of the expert's first chunk and
+// BMX, the rows of an expert split evenly over its chunks in whole 32-row tiles), index of the expert's first chunk and
 // the number of its chunks; *n_tiles their number.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restrict__ idx, int n, int E,
@@ -101,7 +101,9 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
     for (int p = 0; p < E; ++p) {
       const int e = order[p];
       const int nch = (cnt[e] + BMX - 1) / BMX;
-      const int per = nch ? (cnt[e] + nch - 1) / nch : 0;
+      // rows split evenly over the chunks, rounded up to whole 32-row MFMA tiles (the number of
+      // chunks stays nch: (nch - 1) * 256 < cnt)
+      const int per = nch ? ((cnt[e] + nch - 1) / nch + 31) & ~31 : 0;
       const int first = nt;
       for (int m0 = 0; m0 < cnt[e]; m0 += per) {
         int32_t* tl = tiles + TILE_REC * nt;

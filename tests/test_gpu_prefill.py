@@ -123,7 +123,7 @@ def test_fp32_cacheless_prefill_from_host(H):
 
 
 def test_prefill_all_tokens_to_one_expert_and_repeat_calls(H):
-    """Degenerate routing: one expert gets every token (4 chunks of 225 rows that share every
+    """Degenerate routing: one expert gets every token (4 chunks, 3 of 256 rows and one of 132, that share every
     weight tile), the others none; the call is repeatable (workspace reuse) and a smaller batch
     after a larger one is still right."""
     cfg = synth.MoEConfig("t", 128, 256, 4, 1, dtype="bf16", n_tokens=900, seed=24)
