@@ -436,6 +436,19 @@ __device__ __forceinline__ float dot_group(u32x4 q, const float* v, float acc) {
   return acc;
 }
 
+// bf16 weights against the bf16 input vector kept packed, as it is stored: one v_dot2c_f32_bf16
+// per two elements (products exact, sum in fp32) instead of two unpacks and two FMAs.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ float dot_group_packed(u32x4 q, u32x4 xq, float acc) {
+  const bf16x8_t w = __builtin_bit_cast(bf16x8_t, q), xv = __builtin_bit_cast(bf16x8_t, xq);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(xv, xv, 0, 1), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 2, 3), __builtin_shufflevector(xv, xv, 2, 3), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(xv, xv, 4, 5), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 6, 7), __builtin_shufflevector(xv, xv, 6, 7), acc, false);
+  return acc;
+}
+
 // h[i, j] = silu(W1_i[j,:] . x) * (W3_i[j,:] . x).  x in registers (NCH chunks of 64*VEC
 // elements); every wave owns `rpw` consecutive (expert rank, row) pairs, i.e. one long
 // contiguous run of W1 and one of W3.  FULL: H is exactly NCH chunks (constant load offsets).
@@ -448,12 +461,15 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(ExpertSrc src, const in
   constexpr int CHUNK = WAVE * VEC;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const int nvec = H / VEC;
-  float xr[NCH][VEC];
+  constexpr bool PACKED = sizeof(T) == 2;   // bf16: x stays packed for the dot2 instruction
+  float xr[PACKED ? 1 : NCH][VEC];
+  u32x4 xq[PACKED ? NCH : 1];
   int off[NCH];  // element offset of this lane's group in chunk c (clamped into the row)
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const int v = c * WAVE + lane;
-    load_vec_regs<T>(x, v, nvec, xr[c]);
+    if constexpr (PACKED) xq[c] = v < nvec ? load16(x + (size_t)v * VEC) : u32x4{0u, 0u, 0u, 0u};
+    else load_vec_regs<T>(x, v, nvec, xr[c]);
     off[c] = FULL ? c * CHUNK + lane * VEC : (v < nvec ? v : nvec - 1) * VEC;
   }
   const int total = k * F;
@@ -467,11 +483,12 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(ExpertSrc src, const in
     const int nrow = seg_end - r;
     const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
     float* hout = hbuf + (size_t)i * F + j0;
-#pragma unroll 1
-    for (int rr = 0; rr < nrow; ++rr) {
+    // Two row pairs alternate between two register sets: the loads of the next pair are on their
+    // way while the current one is multiplied and reduced, so the wave (one per SIMD) always has
+    // loads in flight.
+    auto issue = [&](int rr, u32x4 (&qa)[NCH], u32x4 (&qb)[NCH]) {
       const T* w1 = base + (size_t)(j0 + rr) * H;
       const T* w3 = w1 + (size_t)F * H;
-      u32x4 qa[NCH], qb[NCH];
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
         if constexpr (FULL) {
@@ -482,16 +499,34 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(ExpertSrc src, const in
           qb[c] = load16_stream(w3 + off[c]);
         }
       }
+    };
+    auto finish = [&](int rr, const u32x4 (&qa)[NCH], const u32x4 (&qb)[NCH]) {
       float a = 0.f, b = 0.f;
 #pragma unroll
       for (int c = 0; c < NCH; ++c) {
-        a = dot_group<T>(qa[c], xr[c], a);
-        b = dot_group<T>(qb[c], xr[c], b);
+        if constexpr (PACKED) {
+          a = dot_group_packed(qa[c], xq[c], a);
+          b = dot_group_packed(qb[c], xq[c], b);
+        } else {
+          a = dot_group<T>(qa[c], xr[c], a);
+          b = dot_group<T>(qb[c], xr[c], b);
+        }
       }
       a = wave_sum(a);
       b = wave_sum(b);
       if (lane == 0) hout[rr] = a / (1.f + expf(-a)) * b;
+    };
+    u32x4 qa0[NCH], qb0[NCH], qa1[NCH], qb1[NCH];
+    int rr = 0;
+    issue(0, qa0, qb0);
+#pragma unroll 1
+    for (; rr + 2 <= nrow; rr += 2) {
+      issue(rr + 1, qa1, qb1);
+      finish(rr, qa0, qb0);
+      if (rr + 2 < nrow) issue(rr + 2, qa0, qb0);
+      finish(rr + 1, qa1, qb1);
     }
+    if (rr < nrow) finish(rr, qa0, qb0);
     r = seg_end;
   }
 }
