@@ -613,8 +613,9 @@ constexpr size_t MAX_LDS = 160 * 1024;
 namespace {
 // Launch-shape overrides for tuning experiments (0 = use the built-in policy); read once from the
 // environment: ODMOE_TUNE_UP_RPW (rows per wave of the w1/w3 GEMV), ODMOE_TUNE_DOWN_RPB (rows
-// per block of the w2 GEMV), ODMOE_TUNE_DOWN_EG (its expert groups per block).
-int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0;
+// per block of the w2 GEMV), ODMOE_TUNE_DOWN_EG (its expert groups per block),
+// ODMOE_TUNE_ROUTE_SPLIT_E (fewest experts for which few-token router calls use several blocks).
+int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0, g_tune_route_split_e = 0;
 int env_int(const char* name) {
   const char* v = getenv(name);
   const int n = v ? atoi(v) : 0;
@@ -624,6 +625,7 @@ int env_int(const char* name) {
 
 hipError_t kernels_init() {
   g_tune_up_rpw = env_int("ODMOE_TUNE_UP_RPW");
+  g_tune_route_split_e = env_int("ODMOE_TUNE_ROUTE_SPLIT_E");
   g_tune_down_rpb = env_int("ODMOE_TUNE_DOWN_RPB");
   g_tune_down_eg = env_int("ODMOE_TUNE_DOWN_EG");
   hipError_t e;
@@ -645,8 +647,10 @@ hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, con
                              int32_t* idx_mirror, const void* const* table, int32_t table_off,
                              const void** eptr_out, const RouteScratch* scratch) {
   if (T <= 0) return hipSuccess;
-  // (up to 32 experts, four rounds of one block cost less than the tickets of the spread variant)
-  if (scratch && scratch->logits && sh.E > 32 && T <= scratch->max_tokens) {
+  // (up to 16 experts, two rounds of one block cost less than the tickets of the spread variant:
+  // 4.3-6.8 us against 6.7-8.1 us; at 32 experts one block takes 18-22 us, the spread variant 9-10)
+  const int split_from = g_tune_route_split_e > 0 ? g_tune_route_split_e : 17;
+  if (scratch && scratch->logits && sh.E >= split_from && T <= scratch->max_tokens) {
     const dim3 grid((sh.E + 7) / 8, T);
     if (sh.dtype == ODMOE_F32)
       route_topk_split_kernel<float><<<grid, 512, 0, s>>>(

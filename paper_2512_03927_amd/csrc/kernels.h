@@ -41,7 +41,7 @@ constexpr int32_t ROUTE_SPLIT_MAX_TOKENS = 16;
 // Router GEMV + top-k + gate for T tokens.  idx_mirror (may be null) is a second int32[T*k]
 // destination (host-mapped pinned memory) written together with idx.  With eptr_out != null the
 // kernel also stores table[table_off + idx] there (T*k pointers), which saves the FFN kernels
-// one dependent load.  With a scratch, more than 32 experts and T <= scratch->max_tokens the
+// one dependent load.  With a scratch, more than 16 experts and T <= scratch->max_tokens the
 // experts of a token are spread over several blocks (same results).
 hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
                              const void* x, int32_t T, int32_t* idx, float* gate,
