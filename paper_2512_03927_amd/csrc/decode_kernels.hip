@@ -437,7 +437,9 @@ __device__ __forceinline__ float dot_group(u32x4 q, const float* v, float acc) {
 }
 
 // bf16 weights against the bf16 input vector kept packed, as it is stored: one v_dot2c_f32_bf16
-// per two elements (products exact, sum in fp32) instead of two unpacks and two FMAs.
+// per two elements (products exact, sum in fp32) instead of two unpacks and two FMAs.  The pairs
+// are cut out of the whole 128-bit value with vector shuffles: bit-casting the 32-bit members
+// (q.x, q.y, ...) one by one made hipcc 7.2 multiply the first pair four times.
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ float dot_group_packed(u32x4 q, u32x4 xq, float acc) {
