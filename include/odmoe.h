@@ -48,6 +48,14 @@
  *     learn which experts to copy, and once at its end), odmoe_expert_ffn in cacheless mode
  *     without idx_host, and odmoe_layer_destroy.
  *   - A handle is not thread-safe: one host thread drives one handle.
+ *
+ * Environment (read by odmoe_layer_init; none is needed):
+ *   ODMOE_COPY_STREAMS=1..8   number of library-owned copy streams, for every case
+ *   ODMOE_TUNE_UP_RPW, ODMOE_TUNE_DOWN_RPB, ODMOE_TUNE_DOWN_EG, ODMOE_TUNE_ROUTE_SPLIT_E
+ *                             launch-shape overrides of the decode kernels for tuning runs
+ *                             (rows per wave, rows per block, expert groups per block, fewest
+ *                             experts for the multi-block router); results do not depend on them
+ *                             except for the order of fp32 additions across expert groups
  */
 #ifndef ODMOE_H
 #define ODMOE_H
