@@ -141,8 +141,8 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //     order in grouped_gemm_kernel) so that the second one finds the weight tile in L2;
 //   - global memory goes straight into LDS (global_load_lds_dwordx4: a wave fills 1 KB = 8 rows of
 //     128 bytes per instruction, every 128-byte line fully coalesced) in a ring of K-steps of one
-//     128-byte line per row (64 bf16 or 32 fp32 elements); no staging registers, one s_barrier per step, and the only vmcnt wait is for the
-//     step about to be used.  The ring holds 3 steps of 40 / 48 KB for up to 64 / 128 rows and 2
+//     128-byte line per row (64 bf16 or 32 fp32 elements); no staging registers, one s_barrier per
+//     step, and the only vmcnt wait is for the step about to be used.  The ring holds 3 steps of 40 / 48 KB for up to 64 / 128 rows and 2
 //     steps of 56 / 64 KB for up to 192 / 256 rows (measured: deeper rings do not help: the CU's
 //     vector L1 keeps only about 125 128-byte requests in flight whatever is queued behind them);
 //   - blocks start their K loops at different steps (kt0): the rows of a row-major matrix lie a
@@ -157,7 +157,10 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //     traffic below MFMA time; NT is a template parameter, so the K loop has no per-tile branches
 //     except the wave-uniform test for the odd tile;
 //   - the 256-row-wide block tile also halves the activation traffic per weight byte.
-//   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+127; out = bf16( silu(A W1^T) * (A W3^T) )
+//   - the two waves a SIMD hosts (one of each M group) share its matrix pipe, so an odd number of
+//     row tiles does not unbalance the SIMDs;
+//   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+127; out = silu(A W1^T) * (A W3^T) in the
+//           element type (bf16 rounded to nearest even, fp32 as computed)
 //   !SILU : halves = weight rows n0..n0+127 / n0+128..n0+255; out = fp32 partial sums for K range
 //           ksplit, [gridDim.z][rows, ldo]
 // K is a multiple of 64.
