@@ -150,7 +150,7 @@ def main() -> int:
         tpath = os.path.join(ROOT, "profiles", "hbm_traffic_cfg2.json")
         if os.path.exists(tpath):
             traffic = json.load(open(tpath)).get("ffn_up_kernel_bytes_per_launch")
-        roofline = {"bound": "hbm", "kernel": "ffn_up_kernel<bf16> (w1/w3 GEMV + SiLU)",
+        roofline = {"bound": "hbm", "kernel": "ffn_up_reg_kernel<unsigned short, 8, true> (w1/w3 GEMV + SiLU, bf16)",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                     "algorithmic_bytes_per_launch": up_bytes, "avg_launch_us": round(up_ms * 1e3, 2),
