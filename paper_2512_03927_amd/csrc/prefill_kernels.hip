@@ -265,9 +265,10 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, E* smem, int ntile
     E* sa = smem + stage * STAGE;
     const int ko = step_offset(kt);
 #pragma unroll
-    for (int i = 0; i < B_INSTR; ++i)
+    for (int i = 0; i < B_INSTR; ++i)   // weights pass through once: non-temporal (cache policy 2 = nt),
+                                        // so they evict fewer of the activation lines other blocks reuse
       __builtin_amdgcn_global_load_lds((global_void_ptr)(b_src[i] + ko),
-                                       (lds_void_ptr)(sa + A_STAGE + (i * 8 + wave) * 8 * BKE), 16, 0, 0);
+                                       (lds_void_ptr)(sa + A_STAGE + (i * 8 + wave) * 8 * BKE), 16, 0, 2);
   };
   // With a two-deep ring only one step is in flight: the weight fills (HBM) go out first and the
   // activation fills (L2 hits) half a step later, which spreads the requests over the step.
