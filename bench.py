@@ -237,8 +237,8 @@ def main() -> int:
         with harness.MoEStack(c32, [layer32]) as st32:
             X32 = harness.to_device(X32_np)
             Y32 = torch.empty_like(X32)
-            for t in range(min(8, args.fp32_tokens)):
-                B.odmoe_decode_step(st32.handle, X32[t], Y32[t], None, None, None)
+            for t in range(max(8, 256)):                  # warm-up (the GPU idled during weight generation)
+                B.odmoe_decode_step(st32.handle, X32[t % args.fp32_tokens], Y32[t % args.fp32_tokens], None, None, None)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
             for t in range(args.fp32_tokens):

@@ -41,9 +41,15 @@ def main(argv) -> int:
         layer = synth.layer_weights(cfg, 0)
         with harness.MoEStack(cfg, [layer]) as st:
             x = harness.to_device(synth.tokens(cfg, n_tok))
+            # the GPU idled while the host generated the layer: about 60 ms of the same kernels bring
+            # it back to its working clocks before anything is recorded
+            warm_us = 0.0
+            while warm_us < 60e3:
+                r, u, d = B.odmoe_time_decode_kernels(st.handle, 0, x, n_tok, 4)
+                warm_us += (r + u + d) * n_tok * 4
             best = None
             for _ in range(3):
-                r, u, d = B.odmoe_time_decode_kernels(st.handle, 0, x, n_tok, 2)
+                r, u, d = B.odmoe_time_decode_kernels(st.handle, 0, x, n_tok, 4)
                 if best is None or u + d < best[1] + best[2]:
                     best = (r, u, d)
         r, u, d = best
