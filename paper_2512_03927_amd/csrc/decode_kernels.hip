@@ -176,26 +176,36 @@ template <typename T>
 __device__ __forceinline__ double wave_logit(const T* __restrict__ row, const T* __restrict__ xt, int nvec,
                                              int lane) {
   constexpr int VEC = DT<T>::VEC;
+  constexpr int U = 8;            // 16-byte groups per lane whose loads are issued together
   double acc0 = 0.0, acc1 = 0.0;  // two chains: half the dependent-FMA latency
-  int v = lane;
-  for (; v + WAVE < nvec; v += 2 * WAVE) {
-    float fw[VEC], fx[VEC], gw[VEC], gx[VEC];
-    DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
-    DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
-    DT<T>::unpack(load16(row + (size_t)(v + WAVE) * VEC), gw);
-    DT<T>::unpack(load16(xt + (size_t)(v + WAVE) * VEC), gx);
+  // All loads of a round go out before the first is used: a row of up to U*64 groups (4096 bf16
+  // elements) costs one memory latency instead of one per pair of groups.
+  for (int g0 = 0; g0 < nvec; g0 += U * WAVE) {   // g0: first group of the round (wave-uniform)
+    u32x4 qw[U], qx[U];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) {
-      acc0 = fma((double)fw[j], (double)fx[j], acc0);
-      acc1 = fma((double)gw[j], (double)gx[j], acc1);
+    for (int u = 0; u < U; ++u) {
+      if (g0 + u * WAVE >= nvec) break;             // whole wave past the end of the row
+      const int v = g0 + u * WAVE + lane;
+      if (v < nvec) {
+        qw[u] = load16(row + (size_t)v * VEC);
+        qx[u] = load16(xt + (size_t)v * VEC);
+      } else {
+        qw[u] = u32x4{0u, 0u, 0u, 0u};
+        qx[u] = u32x4{0u, 0u, 0u, 0u};
+      }
     }
-  }
-  for (; v < nvec; v += WAVE) {
-    float fw[VEC], fx[VEC];
-    DT<T>::unpack(load16(row + (size_t)v * VEC), fw);
-    DT<T>::unpack(load16(xt + (size_t)v * VEC), fx);
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) acc0 = fma((double)fw[j], (double)fx[j], acc0);
+    for (int u = 0; u < U; ++u) {
+      if (g0 + u * WAVE >= nvec) break;
+      float fw[VEC], fx[VEC];
+      DT<T>::unpack(qw[u], fw);
+      DT<T>::unpack(qx[u], fx);
+#pragma unroll
+      for (int j = 0; j < VEC; ++j) {
+        if (u & 1) acc1 = fma((double)fw[j], (double)fx[j], acc1);
+        else acc0 = fma((double)fw[j], (double)fx[j], acc0);
+      }
+    }
   }
   return wave_sum(acc0 + acc1);
 }
