@@ -116,6 +116,41 @@ def test_layer_parity_shapes(H, Hd, F, E, k, dtype):
             check_y(yn[t], Y[t], dtype, batch=True)
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        E = int(rng.integers(1, 25))
+        out.append((8 * int(rng.integers(1, 257)), 8 * int(rng.integers(1, 257)), E,
+                    int(rng.integers(1, min(E, 4) + 1)), "bf16" if rng.random() < 0.6 else "f32"))
+    return out
+
+
+@pytest.mark.parametrize("Hd,F,E,k,dtype", _random_shapes(12, 2024))
+def test_layer_parity_random_small_shapes(H, Hd, F, E, k, dtype):
+    """Seeded random shapes (hidden and ffn any multiple of 8 up to 2048, 1-24 experts): ragged
+    chunks, odd wave counts and every launch-policy branch the fixed list may miss; token by token
+    (GEMVs), as a batch (grouped GEMMs where the shape allows them) and from pinned host memory."""
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=3, router_bias=bool(E % 2), seed=Hd + F)
+    Wg, b, experts = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Y, IDX, G = oracle_tokens(cfg, X, Wg, b, experts)
+    with H.MoEStack(cfg, [(Wg, b, experts)]) as st, \
+            H.MoEStack(cfg, [(Wg, b, experts)], experts_in_host_memory=True) as st_host:
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        assert np.array_equal(idx.cpu().numpy(), IDX)
+        assert np.max(np.abs(gate.cpu().numpy().astype(np.float64) - G)) <= GATE_ATOL
+        for t in range(cfg.n_tokens):
+            args = (idx[t:t + 1].contiguous(), gate[t:t + 1].contiguous(), x[t:t + 1].contiguous())
+            y1 = H.from_device(st.ffn(0, *args))[0]
+            check_y(y1, Y[t], dtype)
+            assert np.array_equal(H.from_device(st_host.ffn(0, *args))[0], y1)   # same bits read in place
+        yn = H.from_device(st.ffn(0, idx, gate, x))
+        for t in range(cfg.n_tokens):
+            check_y(yn[t], Y[t], dtype, batch=True)
+
+
 # ---------------------------------------------------------------- routing edge cases
 @pytest.mark.parametrize("E", [12, 40])   # 40 experts: few-token calls take the multi-block router
 def test_routing_ties_zero_router_and_bias(H, E):
