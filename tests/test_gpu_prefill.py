@@ -63,6 +63,35 @@ def test_prefill_matches_oracle(H, Hd, F, E, k, T, bias):
     assert counts.sum() == T * k
 
 
+def _random_prefill_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        E = int(rng.integers(2, 33))
+        out.append((64 * int(rng.integers(1, 13)), 64 * int(rng.integers(1, 13)), E, int(rng.integers(1, min(E, 4) + 1)),
+                    int(rng.integers(17, 900)), bool(rng.integers(0, 2)), "bf16" if rng.random() < 0.6 else "f32"))
+    return out
+
+
+@pytest.mark.parametrize("Hd,F,E,k,T,bias,dtype", _random_prefill_cases(10, 7))
+def test_prefill_random_shapes(H, Hd, F, E, k, T, bias, dtype):
+    """Seeded random layer shapes, batch sizes and routing skews through the grouped GEMMs: chunk
+    classes of every size, experts with no tokens, K splits, both element types."""
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=T, router_bias=bias, seed=Hd + F + T)
+    Wg, b, experts = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Y, IDX, G = O.moe_layer_tokens(X, Wg, b, experts, k)
+    with H.MoEStack(cfg, [(Wg, b, experts)]) as st:
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        assert np.array_equal(idx.cpu().numpy(), IDX)
+        yn = H.from_device(st.ffn(0, idx, gate, x))
+        if dtype == "f32":
+            assert np.max(np.abs(yn - Y)) <= 1e-4
+        else:
+            _check_tokens(yn, Y, range(T))
+
+
 def test_prefill_unsupported_shape_falls_back_to_per_token_path(H):
     cfg = synth.MoEConfig("t", 264, 520, 4, 2, dtype="bf16", n_tokens=20, seed=22)   # not multiples of 64
     Wg, b, experts = synth.layer_weights(cfg)
