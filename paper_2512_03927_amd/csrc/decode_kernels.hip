@@ -851,23 +851,27 @@ hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
 }
 
 // Plain streaming kernels over a buffer of known size: the measured HBM ceiling next to the
-// GEMVs, and the reference a profiler's byte counters are scaled by.  Each block walks one
-// contiguous span with 128-bit loads, eight in flight per lane.
+// GEMVs, and the reference a profiler's byte counters are scaled by.  128-bit loads; the read
+// kernel gives every wave one contiguous span, the copy kernel every block.
 namespace {
 __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ src, size_t n16,
                                                           uint32_t* __restrict__ sink) {
-  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
-  const size_t b0 = (size_t)blockIdx.x * per, b1 = b0 + per < n16 ? b0 + per : n16;
+  // The assignment the w1/w3 GEMV uses, which is also the fastest plain read found: one block of
+  // four waves per CU, every wave one long contiguous run, sixteen 1 KB loads in flight per wave.
+  const int lane = threadIdx.x & 63;
+  const size_t nw = (size_t)gridDim.x * 4, w = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const size_t per = (n16 + nw - 1) / nw;
+  const size_t b0 = w * per, b1 = b0 + per < n16 ? b0 + per : n16;
   uint32_t acc = 0;
-  size_t i = b0 + threadIdx.x;
-  for (; i + 7 * 256 < b1; i += 8 * 256) {
-    u32x4 q[8];
+  size_t i = b0 + lane;
+  for (; i + 15 * 64 < b1; i += 16 * 64) {
+    u32x4 q[16];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) q[u] = __builtin_nontemporal_load(src + i + u * 256);
+    for (int u = 0; u < 16; ++u) q[u] = __builtin_nontemporal_load(src + i + u * 64);
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc ^= q[u].x ^ q[u].y ^ q[u].z ^ q[u].w;
+    for (int u = 0; u < 16; ++u) acc ^= q[u].x ^ q[u].y ^ q[u].z ^ q[u].w;
   }
-  for (; i < b1; i += 256) { const u32x4 q = src[i]; acc ^= q.x ^ q.y ^ q.z ^ q.w; }
+  for (; i < b1; i += 64) { const u32x4 q = src[i]; acc ^= q.x ^ q.y ^ q.z ^ q.w; }
   if (acc == 0x9e3779b9u) sink[0] = acc;  // practically never: keeps the loads alive
 }
 __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict__ src,
@@ -883,7 +887,7 @@ hipError_t launch_probe(hipStream_t s, void* dst, const void* src, size_t bytes,
   if (n16 == 0) return hipSuccess;
   const int grid = num_cu() * 8;
   if (mode == 1)
-    probe_read_kernel<<<grid, 256, 0, s>>>(static_cast<const u32x4*>(src), n16, static_cast<uint32_t*>(dst));
+    probe_read_kernel<<<num_cu(), 256, 0, s>>>(static_cast<const u32x4*>(src), n16, static_cast<uint32_t*>(dst));
   else
     probe_copy_kernel<<<grid, 256, 0, s>>>(static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), n16);
   return hipGetLastError();
