@@ -28,7 +28,7 @@
  * are bit for bit those of the other modes.  Measured, a token then takes 0.995-1.013 times what
  * copying the same experts with hipMemcpyAsync and computing nothing takes: as fast as the slot
  * pool with perfect hints.  odmoe_stats counts no loads and no copied bytes in this form.
- * Batches work too, but the grouped GEMMs fetch an expert's weights once per chunk of 256 of its
+ * Batches work too, but the grouped GEMMs fetch an expert's weights once per chunk of 320 of its
  * tokens, and host memory is not kept in the GPU's L2: for long prompts a second handle with a
  * slot pool over the same pinned buffers is the faster way (config 4: 50 ms against 66 ms).
  *

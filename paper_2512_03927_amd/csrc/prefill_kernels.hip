@@ -18,7 +18,8 @@
 namespace odmoe {
 namespace {
 
-constexpr int BMX = 256;     // most rows of one expert a block takes (one "chunk")
+constexpr int BMX = 320;     // most rows of one expert a block takes (one "chunk"): ten 32-row tiles, what
+                             // the registers (160 accumulators of 256 per lane) and a two-deep ring allow
 constexpr int BN = 256;      // weight rows per block tile: two 128-row halves (W1 and W3 rows of the
                              // same 128 ffn columns for the first GEMM, 256 consecutive rows for the second)
 constexpr int GEMM_THREADS = 512;
@@ -133,17 +134,18 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 }
 
 // ---------------------------------------------------------------------------------------------
-// Grouped GEMM  C[p, n] = sum_k A[row(p), k] * W_e[n, k]  for one chunk (up to BMX = 256 rows) of
+// Grouped GEMM  C[p, n] = sum_k A[row(p), k] * W_e[n, k]  for one chunk (up to BMX = 320 rows) of
 // one expert e and BN = 256 weight rows (two 128-row halves).  Built around the weight stream,
 // which is what bounds it:
-//   - one block takes all rows of the chunk, so an expert with up to 256 tokens reads its weights
+//   - one block takes all rows of the chunk, so an expert with up to 320 tokens reads its weights
 //     exactly once; the chunks of a larger expert are started together on one XCD (see the block
 //     order in grouped_gemm_kernel) so that the second one finds the weight tile in L2;
 //   - global memory goes straight into LDS (global_load_lds_dwordx4: a wave fills 1 KB = 8 rows of
 //     128 bytes per instruction, every 128-byte line fully coalesced) in a ring of K-steps of one
 //     128-byte line per row (64 bf16 or 32 fp32 elements); no staging registers, one s_barrier per
-//     step, and the only vmcnt wait is for the step about to be used.  The ring holds 3 steps of 40 / 48 KB for up to 64 / 128 rows and 2
-//     steps of 56 / 64 KB for up to 192 / 256 rows (measured: deeper rings do not help: the CU's
+//     step, and the only vmcnt wait is for the step about to be used.  The ring holds 3 steps of
+//     40 / 48 KB for up to 64 / 128 rows and 2 steps of 56 ... 72 KB for up to 192 ... 320 rows
+//     (measured: deeper rings do not help: the CU's
 //     vector L1 keeps only about 125 128-byte requests in flight whatever is queued behind them);
 //   - blocks start their K loops at different steps (kt0): the rows of a row-major matrix lie a
 //     multiple of 4 KB apart, and blocks that walk K in lockstep keep hitting the same memory
@@ -152,11 +154,14 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
 //     that fills slot s of row r fetches piece s ^ (r & 7)), so the MFMA fragment reads are
 //     conflict-free;
 //   - 8 waves as 2 (M) x 4 (N, 32 columns of each 128-row half); the chunk's NT = ceil(rows/32)
-//     row tiles go alternately to the two M groups, and a wave multiplies its (up to four) row
-//     tiles by its two 32-column tiles (8 MFMAs per 6 fragment reads), which keeps LDS read
+//     row tiles go alternately to the two M groups, and a wave multiplies its (up to five) row
+//     tiles by its two 32-column tiles (10 MFMAs per 7 fragment reads), which keeps LDS read
 //     traffic below MFMA time; NT is a template parameter, so the K loop has no per-tile branches
 //     except the wave-uniform test for the odd tile;
-//   - the 256-row-wide block tile also halves the activation traffic per weight byte.
+//   - the 256-row-wide weight tile halves the activation traffic per weight byte, and the tall
+//     chunk (320 rows instead of 256: the 512 tokens of config 4 in 589 instead of 655 us) saves the
+//     second pass over the weights for experts with 257-320 tokens; 384 rows fit too (all 256
+//     registers, 160 KB of LDS) and are no faster;
 //   - the two waves a SIMD hosts (one of each M group) share its matrix pipe, so an odd number of
 //     row tiles does not unbalance the SIMDs;
 //   SILU  : halves = W1 / W3 rows of ffn columns n0..n0+127; out = silu(A W1^T) * (A W3^T) in the
@@ -406,7 +411,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) 
     case 5: gemm_chunk<E, SILU, 5, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
     case 6: gemm_chunk<E, SILU, 6, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
     case 7: gemm_chunk<E, SILU, 7, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
-    default: gemm_chunk<E, SILU, 8, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 8: gemm_chunk<E, SILU, 8, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    case 9: gemm_chunk<E, SILU, 9, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
+    default: gemm_chunk<E, SILU, 10, 2>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
   }
 }
 

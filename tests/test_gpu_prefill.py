@@ -37,7 +37,7 @@ def _check_tokens(yn, Y, toks):
     (320, 576, 8, 2, 16, False),     # smallest batch that takes the grouped path; some experts idle
     (128, 192, 8, 3, 257, True),     # k = 3, odd token count
     (2048, 1408, 64, 6, 48, False),  # fine-grained layer shape, most experts see 0-10 tokens
-    (128, 192, 16, 4, 1500, True),   # 6000 token-slots: experts with 1-4 chunks each, about 35 chunks
+    (128, 192, 16, 4, 1500, True),   # 6000 token-slots: experts with 1-4 chunks each, about 30 chunks
 ])
 def test_prefill_matches_oracle(H, Hd, F, E, k, T, bias):
     cfg = synth.MoEConfig("t", Hd, F, E, k, dtype="bf16", n_tokens=T, router_bias=bias, seed=21)
@@ -113,7 +113,7 @@ def test_prefill_unsupported_shape_falls_back_to_per_token_path(H):
 
 
 @pytest.mark.parametrize("Hd,F,E,k,T,bias", [
-    (256, 512, 4, 2, 600, True),     # chunks of up to 256 rows, ragged tails, skewed routing
+    (256, 512, 4, 2, 600, True),     # chunks of up to 320 rows, ragged tails, skewed routing
     (128, 192, 8, 3, 257, True),     # k = 3, odd token count, K split of the w2 GEMM
     (512, 1024, 8, 2, 16, False),    # config 1's layer shape, smallest batch on the grouped path
     (64, 64, 16, 4, 1500, False),    # one K step per block, about 30 chunks
@@ -152,7 +152,7 @@ def test_fp32_cacheless_prefill_from_host(H):
 
 
 def test_prefill_all_tokens_to_one_expert_and_repeat_calls(H):
-    """Degenerate routing: one expert gets every token (4 chunks, 3 of 256 rows and one of 132, that share every
+    """Degenerate routing: one expert gets every token (3 chunks of 320, 320 and 260 rows that share every
     weight tile), the others none; the call is repeatable (workspace reuse) and a smaller batch
     after a larger one is still right."""
     cfg = synth.MoEConfig("t", 128, 256, 4, 1, dtype="bf16", n_tokens=900, seed=24)
