@@ -127,7 +127,9 @@ typedef struct {
  *                   of consecutive layers no longer finish in issue order).
  *   out         receives the handle.
  * Allocates S*expert_bytes of HBM for the slot pool plus small scratch.  n_slots > 0 needs
- * n_slots >= top_k.  Returns EINVAL / ENOMEM / EHIP; on failure *out is NULL.
+ * n_slots >= top_k.  Expert buffers the HIP runtime knows to be ordinary (unpinned) host memory, or
+ * device memory where n_slots > 0 wants pinned host memory, are refused with EINVAL.  Returns
+ * EINVAL / ENOMEM / EHIP; on failure *out is NULL.
  */
 int odmoe_layer_init(const odmoe_config* cfg, const void* const* router_w,
                      const void* const* router_b, const void* const* expert_w,

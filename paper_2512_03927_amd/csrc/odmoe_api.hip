@@ -385,6 +385,22 @@ static int layer_init_impl(const odmoe_config* cfg, const void* const* router_w,
   } while (0)
 
   INIT_TRY(kernels_init(), ODMOE_EHIP);
+  // Where the expert buffers live.  The runtime knows every device allocation and every pinned host
+  // allocation; memory it has never seen (plain malloc) cannot be read by a kernel and makes a
+  // copy synchronous, so it is refused here instead of faulting later.  A failing query says
+  // nothing and is ignored.
+  for (size_t i = 0; i < h->expert_w.size(); ++i) {
+    hipPointerAttribute_t attr{};
+    if (hipPointerGetAttributes(&attr, h->expert_w[i]) != hipSuccess) {
+      (void)hipGetLastError();
+      continue;
+    }
+    if (attr.type == hipMemoryTypeUnregistered)
+      return fail(ODMOE_EINVAL, "expert_w[%zu] is neither device memory nor pinned host memory", i);
+    if (S > 0 && attr.type != hipMemoryTypeHost)
+      return fail(ODMOE_EINVAL, "expert_w[%zu]: with n_slots > 0 the experts live in pinned host memory", i);
+    if (S == 0 && attr.type == hipMemoryTypeHost) h->sh.host_link = 1;   // read in place over the host link
+  }
   const size_t H = cfg->hidden, F = cfg->ffn;
   INIT_TRY(hipMalloc(&h->hbuf, (size_t)k * F * sizeof(float)), ODMOE_ENOMEM);
   INIT_TRY(hipMalloc(&h->xbuf[0], H * h->esize), ODMOE_ENOMEM);
@@ -406,16 +422,6 @@ static int layer_init_impl(const odmoe_config* cfg, const void* const* router_w,
   INIT_TRY(hipEventCreateWithFlags(&h->route_ev, hipEventDisableTiming), ODMOE_EHIP);
 
   if (S == 0) {
-    // Experts may sit in pinned host memory and be read in place: the GEMVs then take launch
-    // shapes made for the host link.  A pointer the runtime does not know is taken for HBM.
-    for (size_t i = 0; i < h->expert_w.size() && !h->sh.host_link; ++i) {
-      hipPointerAttribute_t attr{};
-      if (hipPointerGetAttributes(&attr, h->expert_w[i]) != hipSuccess) {
-        (void)hipGetLastError();
-        continue;
-      }
-      if (attr.type == hipMemoryTypeHost) h->sh.host_link = 1;
-    }
     INIT_TRY(hipMalloc((void**)&h->eptr_dev, (size_t)L * k * sizeof(void*)), ODMOE_ENOMEM);
     INIT_TRY(hipMalloc((void**)&h->table_dev, (size_t)L * E * sizeof(void*)), ODMOE_ENOMEM);
     INIT_TRY(hipMemcpy((void*)h->table_dev, h->expert_w.data(), (size_t)L * E * sizeof(void*),

@@ -432,6 +432,22 @@ def test_error_paths(H):
         # empty batch is a no-op
         B.odmoe_route_topk(st.handle, 0, x, 0, idx, gate)
     rcfg = synth.MoEConfig("t", 64, 64, 4, 2, dtype="f32")
+    # expert buffers in plain (pageable) host memory: refused at init, in either mode
+    import torch
+    Wg_r, _, experts_r = synth.layer_weights(rcfg)
+    router_dev = H.to_device(Wg_r)
+    for n_slots in (0, 2):
+        c = B.odmoe_config(64, 64, 4, 2, 1, n_slots, B.ODMOE_F32, 0)
+        with pytest.raises(B.OdmoeError) as ei:
+            B.odmoe_layer_init(c, [router_dev], None, [np.ascontiguousarray(e) for e in experts_r],
+                               torch.cuda.current_stream().cuda_stream, None)
+        assert ei.value.code == B.ODMOE_EINVAL
+    # device buffers where the slot pool expects pinned host memory
+    c = B.odmoe_config(64, 64, 4, 2, 1, 2, B.ODMOE_F32, 0)
+    with pytest.raises(B.OdmoeError) as ei:
+        B.odmoe_layer_init(c, [router_dev], None, [H.to_device(e) for e in experts_r],
+                           torch.cuda.current_stream().cuda_stream, None)
+    assert ei.value.code == B.ODMOE_EINVAL
     with H.MoEStack(rcfg) as st:
         with pytest.raises(B.OdmoeError) as ei:
             B.odmoe_expert_load_async(st.handle, 0, 0)
