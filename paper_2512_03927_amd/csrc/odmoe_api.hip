@@ -401,6 +401,17 @@ static int layer_init_impl(const odmoe_config* cfg, const void* const* router_w,
       return fail(ODMOE_EINVAL, "expert_w[%zu]: with n_slots > 0 the experts live in pinned host memory", i);
     if (S == 0 && attr.type == hipMemoryTypeHost) h->sh.host_link = 1;   // read in place over the host link
   }
+  for (int l = 0; l < L; ++l)
+    for (const void* p : {h->router_w[l], h->router_b[l]}) {
+      hipPointerAttribute_t attr{};
+      if (!p) continue;
+      if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        continue;
+      }
+      if (attr.type == hipMemoryTypeUnregistered)
+        return fail(ODMOE_EINVAL, "router weights / bias of layer %d are not in memory the GPU can read", l);
+    }
   const size_t H = cfg->hidden, F = cfg->ffn;
   INIT_TRY(hipMalloc(&h->hbuf, (size_t)k * F * sizeof(float)), ODMOE_ENOMEM);
   INIT_TRY(hipMalloc(&h->xbuf[0], H * h->esize), ODMOE_ENOMEM);

@@ -442,6 +442,11 @@ def test_error_paths(H):
             B.odmoe_layer_init(c, [router_dev], None, [np.ascontiguousarray(e) for e in experts_r],
                                torch.cuda.current_stream().cuda_stream, None)
         assert ei.value.code == B.ODMOE_EINVAL
+    c = B.odmoe_config(64, 64, 4, 2, 1, 0, B.ODMOE_F32, 0)
+    with pytest.raises(B.OdmoeError) as ei:                      # router weights in plain host memory
+        B.odmoe_layer_init(c, [np.ascontiguousarray(Wg_r)], None, [H.to_device(e) for e in experts_r],
+                           torch.cuda.current_stream().cuda_stream, None)
+    assert ei.value.code == B.ODMOE_EINVAL
     # device buffers where the slot pool expects pinned host memory
     c = B.odmoe_config(64, 64, 4, 2, 1, 2, B.ODMOE_F32, 0)
     with pytest.raises(B.OdmoeError) as ei:
