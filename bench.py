@@ -487,6 +487,7 @@ def main() -> int:
         el = time.perf_counter() - t_start
         cpu = {"value": round(args.cpu_tokens / el, 4), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                "sample": f"first {args.cpu_tokens} of the {T} tokens of {cfg.name} (float64 NumPy oracle)",
+               "stored_weight_GBps": round(args.cpu_tokens / el * cfg.top_k * cfg.expert_bytes / 1e9, 2),
                "gpu_vs_oracle_max_rel_err": worst}
         log(f"[bench] cpu oracle: {cpu}")
 
