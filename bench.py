@@ -301,6 +301,7 @@ def main() -> int:
             t_prev = t_now
         torch.cuda.synchronize()
         el = time.perf_counter() - t_start
+        log(f"[bench] {c.name}: {n_tok} tokens without hints in {el:.1f} s")
         pt = np.sort(np.asarray(per_token))
         idx_used = np.zeros((c.n_layers, c.top_k), np.int32)
         B.odmoe_decode_step(stc.handle, xs[0], yc, None, idx_used, s)
@@ -309,6 +310,7 @@ def main() -> int:
             B.odmoe_decode_step(stc.handle, xs[0], yc, idx_used, None, s)
         torch.cuda.synchronize()
         el_hint = time.perf_counter() - t1
+        log(f"[bench] {c.name}: {n_tok} tokens with perfect hints in {el_hint:.1f} s")
         # hints corrupted at the miss rates of the paper's three predictors (Section 3.2: recall
         # 99.94 % / 97.34 % / 95.67 %) and at the 75 % of random prefetching: a wrong hint costs a
         # wasted copy plus a reload, so on a saturated link time grows with the miss rate
@@ -330,6 +332,7 @@ def main() -> int:
                 hits += s.hint_hits
                 loads_r += s.loads
             torch.cuda.synchronize()
+            log(f"[bench] {c.name}: hints with miss rate {miss:g} done")
             by_recall[f"{miss:g}"] = {"recall": round(hits / (n_r * c.n_layers * c.top_k), 4),
                                       "ms_per_token": round((time.perf_counter() - t2) / n_r * 1e3, 3),
                                       "copies_per_token": loads_r // n_r}
@@ -347,6 +350,7 @@ def main() -> int:
                 B.odmoe_decode_step(stc.handle, xs[0], yc, pred, None, s)
             torch.cuda.synchronize()
             late[str(d)] = round((time.perf_counter() - t2) / n_l * 1e3, 3)
+            log(f"[bench] {c.name}: hints withheld for the first {d} layer(s) done")
         s.t_step_ms = -1.0
         B.odmoe_decode_step(stc.handle, xs[0], yc, None, None, s)        # one timed token for the breakdown
         # the same bytes copied with no kernels in between (wall clock, all copy streams)
