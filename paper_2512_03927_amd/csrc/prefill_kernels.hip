@@ -58,7 +58,7 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
 // ---------------------------------------------------------------------------------------------
 // Bucket the n = T*k token-slots by expert.  One block.  Slots with an out-of-range expert id
 // are left out (inv = -1) and contribute nothing.
-// tiles: one record of TILE_REC ints per chunk: expert, first row within the expert, rows (at most
+// tiles: one record of TILE_REC ints per chunk: expert, first row in the sorted order, rows (at most
 // BMX, the rows of an expert split evenly over its chunks in whole 32-row tiles), index of the expert's first chunk and
 // the number of its chunks; *n_tiles their number.
 // ---------------------------------------------------------------------------------------------
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
       for (int m0 = 0; m0 < cnt[e]; m0 += per) {
         int32_t* tl = tiles + TILE_REC * nt;
         tl[0] = e;
-        tl[1] = m0;
+        tl[1] = start[e] + m0;   // first row of the chunk in the sorted order
         tl[2] = (cnt[e] - m0 < per) ? cnt[e] - m0 : per;
         tl[3] = first;
         tl[4] = nch;
@@ -192,7 +192,6 @@ struct GemmArgs {
   int tile_first;               // first chunk-list entry of this launch
   size_t b_off[2];            // element offsets of the two 64-row halves' matrix starts
   int b_row[2];               // first weight row of each half relative to n0
-  const int32_t* offsets;
   const int32_t* tiles;
   const int32_t* n_tiles;
   void* out;
@@ -293,9 +292,9 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, E* smem, int ntile
 
   const int last = nk - 1;
 #pragma unroll
-  for (int st = 0; st < NSTAGE - 1; ++st) {
-    issue_a(st, st < last ? st : last);
+  for (int st = 0; st < NSTAGE - 1; ++st) {   // weights first: their addresses do not wait for the row gather
     issue_b(st, st < last ? st : last);
+    issue_a(st, st < last ? st : last);
   }
   int stage = 0, refill = NSTAGE - 1;
   for (int kt = 0; kt < nk; ++kt) {
@@ -395,14 +394,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void grouped_gemm_kernel(GemmArgs g) 
   // order x + gridDim.x * y) the order is made [group of 8 N tiles][chunk][N tile in the group]:
   // the blocks that share an N tile start together, 8 block ids apart (same XCD), so the weight
   // lines one of them brings into that XCD's L2 are still there for the others.
-  const int first = g.tiles[TILE_REC * slot + 3], nsib = g.tiles[TILE_REC * slot + 4];
-  const int lg = bx + (int)gridDim.x * (slot - first);
-  const int rem = lg % (8 * nsib);
-  const int ntile = lg / (8 * nsib) * 8 + (rem & 7);
-  const int tile = first + (rem >> 3);
-  const int e = g.tiles[TILE_REC * tile];
-  const int row_lo = g.offsets[e] + g.tiles[TILE_REC * tile + 1];
-  const int nrows = g.tiles[TILE_REC * tile + 2];
+  // (One record read gives everything when the expert has a single chunk, the usual case: the
+  // weight fills then start two dependent loads after the block does: record, expert pointer.)
+  const int32_t* rec = g.tiles + TILE_REC * slot;
+  int e = rec[0], row_lo = rec[1], nrows = rec[2];
+  const int first = rec[3], nsib = rec[4];
+  int ntile = bx;
+  if (nsib > 1) {
+    const int lg = bx + (int)gridDim.x * (slot - first);
+    const int rem = lg % (8 * nsib);
+    ntile = lg / (8 * nsib) * 8 + (rem & 7);
+    rec = g.tiles + TILE_REC * (first + (rem >> 3));
+    e = rec[0]; row_lo = rec[1]; nrows = rec[2];
+  }
   switch ((nrows + 31) >> 5) {      // 32-row tiles of the chunk
     case 1: gemm_chunk<E, SILU, 1, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
     case 2: gemm_chunk<E, SILU, 2, 3>(g, smem, ntile, ksplit, e, row_lo, nrows); break;
@@ -569,7 +573,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   g1.A = x; g1.lda = sh.H; g1.a_slot = c.perm; g1.slot_div = sh.k;
   g1.table = table; g1.table_off = table_off; g1.expert_override = expert_override; g1.tile_first = tile_first;
   g1.b_off[0] = 0; g1.b_off[1] = hf; g1.b_row[0] = 0; g1.b_row[1] = 0;        // W1 and W3 rows n0..n0+127
-  g1.offsets = c.offsets; g1.tiles = c.tiles; g1.n_tiles = c.n_tiles;
+  g1.tiles = c.tiles; g1.n_tiles = c.n_tiles;
   g1.out = c.hbuf; g1.ldo = sh.F; g1.N = sh.F; g1.K = sh.H; g1.k_per_split = sh.H; g1.split_stride = 0;
   // x = N tile (fastest; padded to a multiple of the 8 XCDs so that the chunks of one expert that
   // share an N tile land on the same XCD and its L2), y = chunk, z = K split.
@@ -586,7 +590,7 @@ hipError_t prefill_gemms(hipStream_t s, const Shape& sh, const void* const* tabl
   g2.A = c.hbuf; g2.lda = sh.F; g2.a_slot = nullptr; g2.slot_div = 1;
   g2.table = table; g2.table_off = table_off; g2.expert_override = expert_override; g2.tile_first = tile_first;
   g2.b_off[0] = 2 * hf; g2.b_off[1] = 2 * hf; g2.b_row[0] = 0; g2.b_row[1] = 128;  // W2 rows n0..n0+255
-  g2.offsets = c.offsets; g2.tiles = c.tiles; g2.n_tiles = c.n_tiles;
+  g2.tiles = c.tiles; g2.n_tiles = c.n_tiles;
   g2.out = c.ybuf; g2.ldo = sh.H; g2.N = sh.H; g2.K = sh.F; g2.k_per_split = k_per_split;
   g2.split_stride = (size_t)n * sh.H;
   dim3 grid2(pad8((sh.H + BN - 1) / BN), tile_count, n_split);
