@@ -149,8 +149,9 @@ int odmoe_route_topk(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t
 /*
  * On-demand expert loading EL_l (Sections 1, 3.1): enqueue the copy of expert (layer, expert)
  * from pinned host memory into a free HBM slot on a copy stream.  The copy waits (stream
- * side) for the kernels that last read that slot and for an earlier copy into it.  If the expert is already loading or
- * ready, its slot is returned and nothing is copied.  *slot_out (may be NULL) gets the slot.
+ * side) for the kernels that last read that slot and for an earlier copy into it.  If the
+ * expert is already loading or ready, its slot is returned and nothing is copied.  *slot_out
+ * (may be NULL) gets the slot.
  * EBUSY when every slot is occupied; EINVAL in resident mode or for a bad index.
  */
 int odmoe_expert_load_async(odmoe_layer_t* h, int32_t layer, int32_t expert, int32_t* slot_out);
