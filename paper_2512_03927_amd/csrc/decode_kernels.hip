@@ -454,10 +454,14 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 __device__ __forceinline__ float dot_group_packed(u32x4 q, u32x4 xq, float acc) {
   const bf16x8_t w = __builtin_bit_cast(bf16x8_t, q), xv = __builtin_bit_cast(bf16x8_t, xq);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 0, 1), __builtin_shufflevector(xv, xv, 0, 1), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 2, 3), __builtin_shufflevector(xv, xv, 2, 3), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 4, 5), __builtin_shufflevector(xv, xv, 4, 5), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, 6, 7), __builtin_shufflevector(xv, xv, 6, 7), acc, false);
+#define ODMOE_DOT2(A, B)                                                                         \
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(w, w, A, B),                     \
+                                        __builtin_shufflevector(xv, xv, A, B), acc, false)
+  ODMOE_DOT2(0, 1);
+  ODMOE_DOT2(2, 3);
+  ODMOE_DOT2(4, 5);
+  ODMOE_DOT2(6, 7);
+#undef ODMOE_DOT2
   return acc;
 }
 

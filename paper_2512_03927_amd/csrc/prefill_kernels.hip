@@ -360,8 +360,10 @@ __device__ __forceinline__ void gemm_chunk(const GemmArgs& g, E* smem, int ntile
           if (col < g.N) {
             const float a = acc[mt][0][i], b = acc[mt][1][i];
             const float hval = a / (1.f + expf(-a)) * b;
-            if constexpr (sizeof(E) == 2) ((__attribute__((address_space(1))) bf16_t*)g.out)[p * g.ldo + col] = f32_to_bf16(hval);
-            else ((__attribute__((address_space(1))) float*)g.out)[p * g.ldo + col] = hval;
+            if constexpr (sizeof(E) == 2)
+              ((__attribute__((address_space(1))) bf16_t*)g.out)[p * g.ldo + col] = f32_to_bf16(hval);
+            else
+              ((__attribute__((address_space(1))) float*)g.out)[p * g.ldo + col] = hval;
           }
         } else {
 #pragma unroll
