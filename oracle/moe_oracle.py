@@ -35,7 +35,8 @@ Pins (tests/test_oracle_*.py): brute-force subset enumeration, gate sums to 1,
 shift invariance, closed-form softmax case, dense all-experts equivalence,
 k=E / k=1 / identical experts / x=0 / zero-router special cases, scalar
 hand case, SiLU identities, pure-Python triple loops on tiny shapes, expert
-relabelling, unit rms after the glue.  Absolute layer outputs are not printed
+relabelling, unit rms after the glue, both glue branches of the stack re-chained by hand, the
+layer with a supplied selection against an independent dense sum.  Absolute layer outputs are not printed
 anywhere in the paper: beyond those invariants they are parity unpinned.
 """
 from __future__ import annotations
@@ -54,7 +55,7 @@ def widen(a: np.ndarray) -> np.ndarray:
     if a.dtype == np.uint16:
         return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
     if a.dtype in (np.float32, np.float64):
-        return a.astype(np.float64)
+        return a.astype(np.float64, copy=False)   # float64 input is returned as it is (never written to)
     raise TypeError(f"unsupported storage dtype {a.dtype}")
 
 
@@ -183,6 +184,27 @@ def moe_layer(x, Wg, b, experts, k: int):
             ew = split_expert(np.asarray(ew), H, F)
         y = y + g[i] * expert_ffn(ew[0], ew[1], ew[2], x)
     return y, idx, g
+
+
+def moe_layer_given_idx(x, Wg, b, experts, idx):
+    """Steps 1 and 3-5 for one token with the selection (step 2) supplied by the caller.
+
+    idx: the experts to use, in output order (idx[0] is the reference of the gate's exponent).
+    Used by tests to continue a stacked comparison past a layer where two logits tie to within
+    rounding and the kernel's own input made the other, equally valid, choice.  With
+    idx = topk_select(router_logits(...)) it is moe_layer.  Returns (y float64[H], g float64[k]).
+    """
+    H = np.asarray(x).shape[0]
+    idx = np.asarray(idx, dtype=np.int32)
+    g = gate_weights(router_logits(Wg, b, x), idx)
+    y = np.zeros(H, dtype=np.float64)
+    for i in range(idx.shape[0]):
+        ew = experts[int(idx[i])]
+        if not isinstance(ew, tuple):
+            F = np.asarray(ew).shape[0] // (3 * H)
+            ew = split_expert(np.asarray(ew), H, F)
+        y = y + g[i] * expert_ffn(ew[0], ew[1], ew[2], x)
+    return y, g
 
 
 def moe_layer_tokens(X, Wg, b, experts, k: int):

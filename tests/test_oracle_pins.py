@@ -253,6 +253,76 @@ def test_glue_has_unit_rms_and_stack_feeds_layers_in_order():
     assert np.allclose(z, np.array([3.0, -4.0]) / math.sqrt(12.5 + 1e-6), rtol=1e-15)
 
 
+def test_stack_without_glue_chains_the_stored_layer_output():
+    """glue = 0: layer l+1 sees store(y_l), nothing else.  Pinned three ways: a scalar stack worked
+    by hand, an independent re-chaining on random layers, and bf16 storage rounding between layers."""
+    # one expert, H = F = 1: FFN(x) = w2 * silu(w1 x) * (w3 x); two layers chained by hand
+    def ffn1(w1, w3, w2, x):
+        a = w1 * x
+        return w2 * (a / (1.0 + math.exp(-a))) * (w3 * x)
+    l0 = (np.array([[0.3]]), None, [(np.array([[1.5]]), np.array([[-0.7]]), np.array([[2.0]]))])
+    l1 = (np.array([[0.1]]), None, [(np.array([[0.4]]), np.array([[1.1]]), np.array([[-3.0]]))])
+    x0 = np.array([0.8], np.float32)
+    y0 = np.float32(ffn1(1.5, -0.7, 2.0, float(x0[0])))                 # stored as fp32 between layers
+    y1 = np.float32(ffn1(0.4, 1.1, -3.0, float(y0)))
+    xo, IDX, xs = O.stack_decode(x0, [l0, l1], 1, "f32", glue=0)
+    assert abs(float(xs[1][0]) - float(y0)) <= 1e-7 * abs(float(y0)) and abs(float(xo[0]) - float(y1)) <= 2e-7 * abs(float(y1))
+    assert len(xs) == 3 and np.array_equal(xs[2], xo) and (IDX == 0).all()
+    # random layers: re-chain by hand; no residual, no normalisation
+    H, F, E, k, L = 12, 20, 5, 2, 3
+    layers = []
+    for l in range(L):
+        Wg, experts = _rand_layer(H, F, E, seed=300 + l, std=0.6)
+        layers.append((Wg.astype(np.float32), None, [tuple(w.astype(np.float32) for w in ex) for ex in experts]))
+    x0 = np.random.default_rng(5).normal(size=H).astype(np.float32)
+    xo, IDX, xs = O.stack_decode(x0, layers, k, "f32", glue=0)
+    x = x0
+    for l in range(L):
+        y, idx, _ = O.moe_layer(x, *layers[l], k)
+        assert np.array_equal(idx, IDX[l])
+        x = y.astype(np.float32)
+        assert np.array_equal(x, xs[l + 1])
+    assert np.array_equal(xo, x)
+    # the two branches differ (a residual + norm would change the result)
+    assert not np.allclose(O.widen(O.stack_decode(x0, layers, k, "f32", glue=1)[0]), O.widen(xo))
+    # bf16 storage between layers
+    xb = O.round_to_storage(x0.astype(np.float64), "bf16")
+    xo_b, _, xs_b = O.stack_decode(xb, layers[:2], k, "bf16", glue=0)
+    y, _, _ = O.moe_layer(xb, *layers[0], k)
+    assert np.array_equal(xs_b[1], O.round_to_storage(y, "bf16")) and xs_b[1].dtype == np.uint16
+    y2, _, _ = O.moe_layer(xs_b[1], *layers[1], k)
+    assert np.array_equal(xo_b, O.round_to_storage(y2, "bf16"))
+
+
+def test_layer_with_supplied_selection():
+    """moe_layer_given_idx: with the router's own selection it is moe_layer; with any other
+    selection it is the dense sum over all experts with a softmax renormalised on that set (computed
+    here with a library softmax and explicit loops), in the order given."""
+    H, F, E, k = 7, 9, 6, 3
+    Wg, experts = _rand_layer(H, F, E, seed=77)
+    b = np.random.default_rng(4).normal(size=E).astype(np.float32)
+    for t in range(6):
+        x = np.random.default_rng(40 + t).normal(size=H)
+        y_ref, idx, g_ref = O.moe_layer(x, Wg, b, experts, k)
+        y, g = O.moe_layer_given_idx(x, Wg, b, experts, idx)
+        assert np.array_equal(y, y_ref) and np.array_equal(g, g_ref)
+        other = np.random.default_rng(t).permutation(E)[:k]
+        y2, g2 = O.moe_layer_given_idx(x, Wg, b, experts, other)
+        p = scipy.special.softmax(O.router_logits(Wg, b, x).astype(np.float64))
+        keep = np.zeros(E)
+        keep[other] = p[other]
+        keep /= keep.sum()
+        dense = np.zeros(H)
+        for e in range(E):
+            W1, W3, W2 = experts[e]
+            h = [sum(W1[j, i] * x[i] for i in range(H)) for j in range(F)]
+            u = [sum(W3[j, i] * x[i] for i in range(H)) for j in range(F)]
+            hv = [h[j] / (1.0 + math.exp(-h[j])) * u[j] for j in range(F)]
+            dense += keep[e] * np.array([sum(W2[r, j] * hv[j] for j in range(F)) for r in range(H)])
+        assert np.allclose(y2, dense, rtol=1e-11, atol=1e-13)
+        assert np.allclose(g2, keep[other], rtol=1e-12) and abs(g2.sum() - 1) < 1e-12
+
+
 # ------------------------------------------------------------------ storage rounding
 def test_bf16_rounding_matches_library_and_handles_ties_to_even():
     torch = pytest.importorskip("torch")
