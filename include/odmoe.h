@@ -25,12 +25,10 @@
  * held in HBM at all, the GEMV kernels pull the activated experts' weights across the host
  * link while they compute (launch shapes made for the link: about a hundred waves, each streaming
  * one long run), no host synchronisation happens per layer, no prediction is needed, and results
- * are bit for bit those of the other modes.  Measured, a token then takes 0.995-1.013 times what
- * copying the same experts with hipMemcpyAsync and computing nothing takes: as fast as the slot
- * pool with perfect hints.  odmoe_stats counts no loads and no copied bytes in this form.
- * Batches work too, but the grouped GEMMs fetch an expert's weights once per chunk of 320 of its
- * tokens, and host memory is not kept in the GPU's L2: for long prompts a second handle with a
- * slot pool over the same pinned buffers is the faster way (config 4: 50 ms against 66 ms).
+ * are bit for bit those of the other modes.  odmoe_stats counts no loads and no copied bytes in
+ * this form.  Batches work too, but the grouped GEMMs fetch an expert's weights once per chunk of
+ * 320 of its tokens, and host memory is not kept in the GPU's L2: for long prompts a second handle
+ * with a slot pool over the same pinned buffers is the faster way.
  *
  * Conventions.
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
@@ -48,14 +46,15 @@
  *     learn which experts to copy, and once at its end), odmoe_expert_ffn in cacheless mode
  *     without idx_host, and odmoe_layer_destroy.
  *   - A handle is not thread-safe: one host thread drives one handle.
+ *   - After a failing call a cacheless handle stays usable: odmoe_decode_step waits for the work
+ *     in flight and frees every slot (experts loaded earlier through odmoe_expert_load_async
+ *     included); odmoe_expert_ffn gives back the slots that the call itself took.
  *
- * Environment (read by odmoe_layer_init; none is needed):
- *   ODMOE_COPY_STREAMS=1..8   number of library-owned copy streams, for every case
- *   ODMOE_TUNE_UP_RPW, ODMOE_TUNE_DOWN_RPB, ODMOE_TUNE_DOWN_EG, ODMOE_TUNE_ROUTE_SPLIT_E
- *                             launch-shape overrides of the decode kernels for tuning runs
- *                             (rows per wave, rows per block, expert groups per block, fewest
- *                             experts for the multi-block router); results do not depend on them
- *                             except for the order of fp32 additions across expert groups
+ * Environment (read by odmoe_layer_init; not needed):
+ *   ODMOE_COPY_STREAMS=1..8   number of library-owned copy streams (changes timing only)
+ *
+ * Measurement aids (a streaming probe, per-kernel timings, a copy-only replay) are declared in
+ * odmoe_measure.h; they are not part of the method.
  */
 #ifndef ODMOE_H
 #define ODMOE_H
@@ -163,10 +162,10 @@ int odmoe_expert_evict(odmoe_layer_t* h, int32_t layer, int32_t expert);
 /*
  * Expert computation EC_l (Section 3.1) with the weighted combine, for n_tokens tokens:
  *   y[t] = sum_i gate[t,i] * FFN_{idx[t,i]}(x[t]).
- *   idx_dev[T,k], gate_dev[T,k], x_dev[T,H], y_dev[T,H] are device pointers.  Every idx entry
- *   must be an expert id in [0, n_experts), as odmoe_route_topk writes them: the per-token
- *   kernels use it unchecked to pick the expert's weights (the library cannot see device memory
- *   without blocking); the grouped path leaves an out-of-range slot out of the sum.
+ *   idx_dev[T,k], gate_dev[T,k], x_dev[T,H], y_dev[T,H] are device pointers.  An idx entry
+ *   outside [0, n_experts) selects no expert: that rank is left out of the sum (the kernels test
+ *   it; the library cannot see device memory without blocking).  In cacheless mode such an entry
+ *   in the host copy of one token's ids is EINVAL.
  *   idx_host   optional host copy of idx (cacheless mode needs to know the experts on the
  *              host; when NULL there, the library reads idx_dev back and blocks for it).
  *   n_tokens   resident mode: token by token (one fused w1/w3+SiLU GEMV and one w2+combine GEMV
@@ -218,35 +217,6 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
 /* Pinned host memory for the expert store (the workers' DRAM of Section 1). */
 int odmoe_pinned_alloc(uint64_t bytes, void** out_host);
 int odmoe_pinned_free(void* host);
-
-/*
- * Measurement aid (not part of the paper's method): a plain streaming kernel over `bytes`
- * (multiple of 16) of device memory, enqueued on `stream`.  mode 0 copies src_dev to dst_dev
- * (both `bytes` long); mode 1 only reads src_dev (dst_dev: at least 4 bytes of scratch).  It
- * gives the measured HBM ceiling the expert GEMVs are compared with, and a kernel of known
- * traffic to scale a profiler's byte counters by.
- */
-int odmoe_probe_hbm(void* dst_dev, const void* src_dev, uint64_t bytes, int32_t mode, void* stream);
-
-/*
- * Measurement aid: average duration, in microseconds, of each decode kernel of layer `layer`
- * (resident mode) over the n_tokens rows of x_dev[T,H], taken with HIP events on the compute
- * stream around `reps` passes in which the same kernel is launched back to back for every token
- * (token t uses the experts the router picks for it, as in odmoe_decode_step).  Blocks.
- * Allocates and frees small temporaries.
- */
-int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev, int32_t n_tokens,
-                              int32_t reps, float* route_us, float* ffn_up_us, float* ffn_down_us);
-
-/*
- * Measurement aid: the host->HBM copies of `n_tokens` decode tokens (n_layers * top_k expert
- * copies each, layer l taking experts (l*top_k + i) mod n_experts) issued exactly as
- * odmoe_decode_step issues them (same copy streams, slots taken round-robin) but with no kernels
- * in between: *ms_per_token gets the wall-clock time per token.  This is the "load" leg of
- * max(compute, load) a cacheless step is compared with.  Cacheless mode only; ESTATE while an
- * expert holds a slot.  Blocks.
- */
-int odmoe_time_expert_loads(odmoe_layer_t* h, int32_t n_tokens, float* ms_per_token);
 
 /*
  * Longest expert-loading time that causes no compute stall (Section 3.1, load-window

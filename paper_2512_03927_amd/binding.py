@@ -18,7 +18,7 @@ ODMOE_F32, ODMOE_BF16 = 0, 1
 ODMOE_MAX_TOPK = 8
 ODMOE_MAX_EXPERTS = 1024
 
-# every symbol include/odmoe.h declares
+# every symbol include/odmoe.h and include/odmoe_measure.h declare
 EXPORTS = (
     "odmoe_layer_init", "odmoe_layer_destroy", "odmoe_route_topk", "odmoe_expert_load_async",
     "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_decode_step", "odmoe_pinned_alloc",

@@ -75,9 +75,14 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
+// Base address of the expert of rank i, or null when idx[i] is not an expert id (ids reach the
+// table path from the caller's device memory, which the host cannot check without blocking):
+// such a rank is left out of the sum, as in the grouped path.  The answer is wave-uniform.
 __device__ __forceinline__ const void* expert_ptr(const ExpertSrc& s, const int32_t* idx, int i) {
   if (s.resolved) return s.resolved[i];
-  return s.table ? s.table[s.table_off + idx[i]] : s.slot[i];
+  if (!s.table) return s.slot[i];
+  const uint32_t e = (uint32_t)idx[i];
+  return e < (uint32_t)s.n_experts ? s.table[s.table_off + e] : nullptr;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -332,6 +337,7 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(ExpertSrc src, const int32_
     if (r >= total) break;
     const int i = (int)(r / F), j = (int)(r % F);
     const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
+    if (!base) continue;   // not an expert id: the w2 kernel skips this rank too
     const T* w1 = base + (size_t)j * H;
     const T* w3 = base + (size_t)F * H + (size_t)j * H;
     float a, b;
@@ -358,11 +364,13 @@ __global__ __launch_bounds__(512) void ffn_down_kernel(ExpertSrc src, const int3
 #pragma unroll
   for (int rr = 0; rr < RPW; ++rr) acc[rr] = 0.f;
   for (int i = 0; i < k; ++i) {
-    if (i) __syncthreads();
+    const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
+    if (!base) continue;   // the same for every thread of the block
+    __syncthreads();
     stage_vec<float, VEC>(hbuf + (size_t)i * F, svec, F);
     __syncthreads();
     const float g = gate[i];
-    const T* w2 = static_cast<const T*>(expert_ptr(src, idx, i)) + (size_t)2 * F * H;
+    const T* w2 = base + (size_t)2 * F * H;
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
       const int r = r0 + rr;
@@ -498,6 +506,7 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(ExpertSrc src, const in
     const int seg_end = ((i + 1) * F < r_end) ? (i + 1) * F : r_end;
     const int nrow = seg_end - r;
     const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
+    if (!base) { r = seg_end; continue; }   // not an expert id: the w2 kernel skips this rank too
     float* hout = hbuf + (size_t)i * F + j0;
     // Two row pairs alternate between two register sets: the loads of the next pair are on their
     // way while the current one is multiplied and reduced, so the wave (one per SIMD) always has
@@ -577,7 +586,9 @@ __global__ __launch_bounds__(CPW <= 4 ? 1024 : 512) void ffn_down_reg_kernel(Exp
   }
   for (int i = eg; i < k; i += n_eg) {
     const float g = gate[i];
-    const T* w2 = static_cast<const T*>(expert_ptr(src, idx, i)) + (size_t)2 * F * H;
+    const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
+    if (!base) continue;
+    const T* w2 = base + (size_t)2 * F * H;
     const float* hv = hbuf + (size_t)i * F;
     float hr[CPW][VEC];
 #pragma unroll
@@ -627,23 +638,30 @@ constexpr size_t MAX_LDS = 160 * 1024;
 }  // namespace
 
 namespace {
-// Launch-shape overrides for tuning experiments (0 = use the built-in policy); read once from the
-// environment: ODMOE_TUNE_UP_RPW (rows per wave of the w1/w3 GEMV), ODMOE_TUNE_DOWN_RPB (rows
-// per block of the w2 GEMV), ODMOE_TUNE_DOWN_EG (its expert groups per block),
-// ODMOE_TUNE_ROUTE_SPLIT_E (fewest experts for which few-token router calls use several blocks).
+// Launch-shape overrides for tuning sweeps, compiled in only with -DODMOE_TUNING (never in the
+// library that ships: the expert-group count changes the order of fp32 additions).  0 = the
+// built-in policy.  Read once from the environment: ODMOE_TUNE_UP_RPW (rows per wave of the w1/w3
+// GEMV), ODMOE_TUNE_DOWN_RPB (rows per block of the w2 GEMV), ODMOE_TUNE_DOWN_EG (its expert
+// groups per block), ODMOE_TUNE_ROUTE_SPLIT_E (fewest experts for the multi-block router).
+#ifdef ODMOE_TUNING
 int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0, g_tune_route_split_e = 0;
 int env_int(const char* name) {
   const char* v = getenv(name);
   const int n = v ? atoi(v) : 0;
   return n > 0 ? n : 0;
 }
+#else
+constexpr int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0, g_tune_route_split_e = 0;
+#endif
 }  // namespace
 
 hipError_t kernels_init() {
+#ifdef ODMOE_TUNING
   g_tune_up_rpw = env_int("ODMOE_TUNE_UP_RPW");
   g_tune_route_split_e = env_int("ODMOE_TUNE_ROUTE_SPLIT_E");
   g_tune_down_rpb = env_int("ODMOE_TUNE_DOWN_RPB");
   g_tune_down_eg = env_int("ODMOE_TUNE_DOWN_EG");
+#endif
   hipError_t e;
   const int big = (int)MAX_LDS;
 #define ODMOE_SET_LDS(fn)                                                                    \

@@ -52,4 +52,5 @@ int odmoe_sim_n_free(void* p) { return static_cast<HostSim*>(p)->pool.n_free(); 
 int odmoe_sim_pool_acquire(void* p, int layer, int expert) { return static_cast<HostSim*>(p)->pool.acquire(layer, expert); }
 int odmoe_sim_pool_find(void* p, int layer, int expert) { return static_cast<HostSim*>(p)->pool.find(layer, expert); }
 int odmoe_sim_pool_release(void* p, int slot) { return static_cast<HostSim*>(p)->pool.release(slot) ? 0 : -1; }
+void odmoe_sim_pool_release_all(void* p) { static_cast<HostSim*>(p)->pool.release_all(); }
 }

@@ -10,13 +10,15 @@ namespace odmoe {
 
 // Where the weights of the i-th selected expert (rank i in idx) live.
 //   resolved : resolved != nullptr, pointer = resolved[i]   (device array the router kernel filled)
-//   resident : table != nullptr, pointer = table[table_off + idx[i]]   (device table, L*E entries)
+//   resident : table != nullptr, pointer = table[table_off + idx[i]]   (device table, L*E entries);
+//              idx[i] outside [0, n_experts) selects nothing: that rank adds nothing to y
 //   cacheless: otherwise, pointer = slot[i]                            (HBM slot bases by rank)
 struct ExpertSrc {
   const void* slot[ODMOE_MAX_TOPK];
   const void* const* table;
   const void* const* resolved;
   int32_t table_off;
+  int32_t n_experts;
 };
 
 struct Shape {
@@ -59,9 +61,9 @@ hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
 // glue = 1: x_next = rmsnorm(x + y) (eps 1e-6).  All [H] in sh.dtype.
 hipError_t launch_glue(hipStream_t s, const Shape& sh, const void* x, const void* y, void* x_next);
 
-// Prefill (bf16, resident): tokens grouped by expert, grouped GEMMs on the matrix cores.
+// Prefill (bf16 and fp32 layers): tokens grouped by expert, grouped GEMMs on the matrix cores.
 // Workspace sizes in bytes for T tokens; the workspace is carved by the launcher.
-bool prefill_supported(const Shape& sh);  // bf16 and H, F multiples of 64
+bool prefill_supported(const Shape& sh);  // H and F multiples of 64
 size_t prefill_workspace_bytes(const Shape& sh, int32_t T);
 hipError_t launch_prefill(hipStream_t s, const Shape& sh, const void* const* table,
                           int32_t table_off, const int32_t* idx, const float* gate, const void* x,

@@ -14,6 +14,7 @@
 #include <string>
 #include <vector>
 
+#include "../../include/odmoe_measure.h"
 #include "kernels.h"
 #include "sched.hpp"
 
@@ -217,6 +218,19 @@ int run_ffn_one_token(odmoe_layer* h, const ExpertSrc& src, const int32_t* idx_d
   return ODMOE_OK;
 }
 
+// A cacheless call failed after it had taken slots.  Everything in flight is waited for (the
+// kernels that may still read a slot, the copies that may still write one) and every slot is
+// freed, so the handle can be used again.  Errors of the waits are not reported: the call
+// already has one.
+void abandon_slots(odmoe_layer* h) {
+  if (!h || !h->pool) return;
+  (void)hipStreamSynchronize(h->compute);
+  for (hipStream_t cs : h->copy_ring) (void)hipStreamSynchronize(cs);
+  (void)hipGetLastError();
+  h->pool->release_all();
+  std::fill(h->done_pending.begin(), h->done_pending.end(), 0);
+}
+
 }  // namespace
 
 extern "C" {
@@ -283,6 +297,7 @@ int odmoe_time_decode_kernels(odmoe_layer_t* h, int32_t layer, const void* x_dev
   ExpertSrc src{};
   src.table = h->table_dev;
   src.table_off = layer * h->cfg.n_experts;
+  src.n_experts = h->cfg.n_experts;
   const float* bias = static_cast<const float*>(h->router_b[layer]);
   // warm-up + the routing every later launch uses
   T_TRY(launch_route_topk(h->compute, h->sh, h->router_w[layer], bias, x_dev, n_tokens, idx, gate, nullptr,
@@ -568,6 +583,7 @@ static int expert_ffn_impl(odmoe_layer_t* h, int32_t layer, const int32_t* idx_d
     ExpertSrc src{};
     src.table = h->table_dev;
     src.table_off = layer * E;
+    src.n_experts = E;
     // Tokens grouped by expert read each expert once; token by token reads k experts per token:
     // grouping pays as soon as the token-slots outnumber the experts (and always from 16 tokens).
     if ((n_tokens >= 16 || (int64_t)n_tokens * k > E) && prefill_supported(h->sh)) {
@@ -606,29 +622,40 @@ static int expert_ffn_impl(odmoe_layer_t* h, int32_t layer, const int32_t* idx_d
     HIP_TRY(prefill_sort(h->compute, h->sh, idx_dev, n_tokens, h->prefill_ws, h->prefill_ws_bytes));
     std::vector<int32_t> order(E);
     prefill_expert_order(count.data(), E, order.data());   // the order of the device's chunk list
-    int tile_first = 0;
-    for (int p = 0; p < E; ++p) {
-      const int e = order[p];
-      const int tiles_e = prefill_chunks_of(count[e]);
-      if (tiles_e == 0) continue;
-      int s = h->pool->find(layer, e);
-      if (s < 0) {
-        s = h->pool->acquire(layer, e);
-        if (s < 0) return fail(ODMOE_EBUSY, "all %d slots are occupied", h->cfg.n_slots);
-        if ((rc = enqueue_load(h, layer, e, s))) {
-          h->pool->release(s);
-          return rc;
+    // Slots this call took and still holds: a failure part-way gives them back (the kernels
+    // that read them are waited for first), so that the handle stays usable.
+    std::vector<int> taken;
+    auto stream_experts = [&]() -> int {
+      int tile_first = 0;
+      for (int p = 0; p < E; ++p) {
+        const int e = order[p];
+        const int tiles_e = prefill_chunks_of(count[e]);
+        if (tiles_e == 0) continue;
+        int s = h->pool->find(layer, e);
+        if (s < 0) {
+          s = h->pool->acquire(layer, e);
+          if (s < 0) return fail(ODMOE_EBUSY, "all %d slots are occupied", h->cfg.n_slots);
+          taken.push_back(s);
+          if ((rc = enqueue_load(h, layer, e, s))) return rc;
         }
+        HIP_TRY(hipStreamWaitEvent(h->compute, h->ready_ev[s], 0));
+        HIP_TRY(prefill_gemms(h->compute, h->sh, nullptr, 0, h->pool_mem + (size_t)s * h->expert_bytes,
+                              tile_first, tiles_e, x_dev, n_tokens, h->prefill_ws));
+        if ((rc = mark_used(h, s))) return rc;
+        if (evict_after && h->pool->release(s)) taken.erase(std::remove(taken.begin(), taken.end(), s), taken.end());
+        tile_first += tiles_e;
       }
-      HIP_TRY(hipStreamWaitEvent(h->compute, h->ready_ev[s], 0));
-      HIP_TRY(prefill_gemms(h->compute, h->sh, nullptr, 0, h->pool_mem + (size_t)s * h->expert_bytes,
-                            tile_first, tiles_e, x_dev, n_tokens, h->prefill_ws));
-      if ((rc = mark_used(h, s))) return rc;
-      if (evict_after) h->pool->release(s);
-      tile_first += tiles_e;
+      HIP_TRY(prefill_combine(h->compute, h->sh, gate_dev, n_tokens, y_dev, h->prefill_ws));
+      return ODMOE_OK;
+    };
+    rc = stream_experts();
+    if (rc != ODMOE_OK) {
+      (void)hipStreamSynchronize(h->compute);
+      for (hipStream_t cs : h->copy_ring) (void)hipStreamSynchronize(cs);
+      (void)hipGetLastError();
+      for (int s : taken) h->pool->release(s);
     }
-    HIP_TRY(prefill_combine(h->compute, h->sh, gate_dev, n_tokens, y_dev, h->prefill_ws));
-    return ODMOE_OK;
+    return rc;
   }
 
   // cacheless decode (n_tokens == 1)
@@ -747,6 +774,7 @@ static int decode_step_impl(odmoe_layer_t* h, const void* x_dev, void* y_dev,
     } else {
       src.table = h->table_dev;
       src.table_off = l * E;
+      src.n_experts = E;
       src.resolved = h->eptr_dev + (size_t)l * k;
     }
 
@@ -825,7 +853,11 @@ static int decode_step_impl(odmoe_layer_t* h, const void* x_dev, void* y_dev,
 
 int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
                       const int32_t* predicted_idx_host, int32_t* idx_out_host, odmoe_stats* stats) {
-  return guarded([&] { return decode_step_impl(h, x_dev, y_dev, predicted_idx_host, idx_out_host, stats); });
+  const int rc =
+      guarded([&] { return decode_step_impl(h, x_dev, y_dev, predicted_idx_host, idx_out_host, stats); });
+  // a token that failed part-way leaves hinted and loaded experts in their slots: give them back
+  if (rc != ODMOE_OK && rc != ODMOE_EINVAL) abandon_slots(h);
+  return rc;
 }
 
 }  // extern "C"

@@ -50,6 +50,11 @@ class SlotPool {
     free_.push_back(s);
     return true;
   }
+  // Every occupied slot becomes free (a call failed part-way: what it had loaded is not kept).
+  void release_all() {
+    for (int s = 0; s < (int)slots_.size(); ++s)
+      if (slots_[s].occupied) release(s);
+  }
 
  private:
   std::vector<Slot> slots_;

@@ -53,7 +53,7 @@ class MoEStack:
     def __init__(self, cfg: synth.MoEConfig, layers: Optional[Sequence[LayerWeights]] = None,
                  unique_layers: Optional[int] = None, device: str = "cuda:0",
                  copy_stream: Optional[torch.cuda.Stream] = None, experts_in_host_memory: bool = False,
-                 buffers_of: Optional["MoEStack"] = None):
+                 buffers_of: Optional["MoEStack"] = None, buffer_layers: Optional[Sequence[int]] = None):
         """layers: per-layer stored weights; generated from `cfg` when None.
 
         experts_in_host_memory (with cfg.n_slots == 0): the experts stay in pinned host memory and
@@ -63,7 +63,8 @@ class MoEStack:
         l mod U (same bytes moved per token, less host memory).
 
         buffers_of: another stack of the same layers whose router and expert buffers this one
-        shares instead of making its own copies (it must outlive this stack's use).
+        shares instead of making its own copies (it must outlive this stack's use);
+        buffer_layers picks which of its unique layers, in order (default: all of them).
         """
         self.cfg = cfg
         self.device = device
@@ -80,6 +81,9 @@ class MoEStack:
         uniq_router, uniq_bias, uniq_experts = [], [], []
         if buffers_of is not None:
             uniq_router, uniq_bias, uniq_experts = buffers_of._keep
+            if buffer_layers is not None:
+                uniq_router, uniq_bias, uniq_experts = ([lst[i] for i in buffer_layers]
+                                                        for lst in (uniq_router, uniq_bias, uniq_experts))
             assert len(uniq_experts) == nl
         for (Wg, b, experts) in ([] if buffers_of is not None else self.layers_np):
             uniq_router.append(to_device(Wg, device))

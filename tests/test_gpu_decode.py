@@ -197,6 +197,33 @@ def test_routing_ties_zero_router_and_bias(H, E):
         assert (H.from_device(st.ffn(0, i0, g0, x0)) == 0).all()
 
 
+def test_idx_that_is_no_expert_id_selects_nothing(H):
+    """idx comes from the caller's device memory.  An entry outside [0, E) must not be used as a
+    table index: on the per-token path that rank is left out of the sum, as on the grouped path."""
+    import torch
+    cfg = synth.MoEConfig("t", 264, 520, 6, 3, dtype="bf16", n_tokens=2, seed=9)
+    Wg, b, experts = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    with H.MoEStack(cfg, [(Wg, b, experts)]) as st:
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        assert x.shape[0] * cfg.top_k <= cfg.n_experts           # per-token GEMV path
+        bad = idx.clone()
+        bad[0, 1] = 1 << 20
+        bad[1, 0] = -7
+        yb = H.from_device(st.ffn(0, bad, gate, x))
+        ids, g = idx.cpu().numpy(), gate.cpu().numpy().astype(np.float64)
+        for t, skip in ((0, 1), (1, 0)):
+            ref = np.zeros(cfg.hidden)
+            for i in range(cfg.top_k):
+                if i != skip:
+                    ref += g[t, i] * O.expert_ffn(*O.split_expert(experts[ids[t, i]], cfg.hidden, cfg.ffn), X[t])
+            check_y(yb[t], ref, "bf16")
+        y_ok = H.from_device(st.ffn(0, idx, gate, x))             # and the handle is fine afterwards
+        Y, _, _ = oracle_tokens(cfg, X, Wg, b, experts)
+        check_y(y_ok[0], Y[0], "bf16")
+
+
 def test_multi_block_router_is_repeatable(H):
     """The router variant that spreads a token's experts over several blocks relies on a ticket
     counter that every launch leaves at zero: many launches in a row, with varying token counts,

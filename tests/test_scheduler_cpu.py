@@ -24,7 +24,7 @@ def sim():
     lib.odmoe_sim_new.argtypes = [C.c_int] * 4
     for n in ("odmoe_sim_del", "odmoe_sim_begin", "odmoe_sim_before_route", "odmoe_sim_after_route",
               "odmoe_sim_after_compute", "odmoe_sim_counters", "odmoe_sim_n_free", "odmoe_sim_pool_acquire",
-              "odmoe_sim_pool_find", "odmoe_sim_pool_release"):
+              "odmoe_sim_pool_find", "odmoe_sim_pool_release", "odmoe_sim_pool_release_all"):
         getattr(lib, n).argtypes = None
     return lib
 
@@ -142,6 +142,36 @@ def test_slot_pool_fifo_and_errors(sim):
     # oldest-released slot is reused first
     assert sim.odmoe_sim_pool_acquire(h, 0, 5) == 1 and sim.odmoe_sim_pool_acquire(h, 0, 6) == 0
     assert sim.odmoe_sim_pool_release(h, 7) == -1
+    sim.odmoe_sim_del(h)
+
+
+def test_recovery_after_a_token_that_failed_part_way(sim):
+    """What the library does when a decode step fails between layers: every slot is given back,
+    whatever held it (hinted experts of later layers, the failing layer's own), and the next token
+    runs as on a fresh handle."""
+    L, E, k, S = 8, 8, 2, 6
+    actual = _routes(L, E, k, 5)
+    h = C.c_void_p(sim.odmoe_sim_new(L, E, k, S))
+    buf = np.zeros(4 * 64, dtype=np.int32)
+    sim.odmoe_sim_begin(h, _p(actual))
+    assert sim.odmoe_sim_before_route(h, 0, _p(buf), len(buf)) == S       # three layers' experts hinted ahead
+    slots = np.full(k, -1, dtype=np.int32)
+    sim.odmoe_sim_after_route(h, 0, _p(actual[0]), _p(slots), _p(buf), len(buf))
+    assert sim.odmoe_sim_n_free(h) == 0                                    # ... the token "fails" here
+    sim.odmoe_sim_pool_release_all(h)
+    assert sim.odmoe_sim_n_free(h) == S
+    assert all(sim.odmoe_sim_pool_find(h, l, int(e)) == -1 for l in range(L) for e in range(E))
+    sim.odmoe_sim_pool_release_all(h)                                      # idempotent
+    assert sim.odmoe_sim_n_free(h) == S
+    # the next token on the same pool behaves as on a fresh one
+    sim.odmoe_sim_begin(h, None)
+    for l in range(L):
+        assert sim.odmoe_sim_before_route(h, l, _p(buf), len(buf)) == 0
+        assert sim.odmoe_sim_after_route(h, l, _p(actual[l]), _p(slots), _p(buf), len(buf)) == k
+        assert sim.odmoe_sim_after_compute(h, l, _p(actual[l]), _p(buf), len(buf)) == k
+    loads, reloads, hits = C.c_uint64(), C.c_uint64(), C.c_uint64()
+    sim.odmoe_sim_counters(h, C.byref(loads), C.byref(reloads), C.byref(hits))
+    assert (loads.value, reloads.value, hits.value) == (L * k, 0, 0) and sim.odmoe_sim_n_free(h) == S
     sim.odmoe_sim_del(h)
 
 
