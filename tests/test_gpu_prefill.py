@@ -172,11 +172,18 @@ def test_prefill_all_tokens_to_one_expert_and_repeat_calls(H):
         assert np.array_equal(y_c, y_a[:40])
 
 
-def test_cfg4_full_size_prefill_sampled_tokens(H):
-    """Config 4 as stated: Mixtral-shaped layer, 512 tokens, router bias N(0,1).  Routing is checked
-    for every token; outputs for sampled tokens (the oracle needs about a second per token)."""
+# Measured bound of the bf16 prefill path at full size (the SwiGLU intermediate is rounded to bf16
+# before the w2 GEMM, the oracle rounds nothing): the largest error over all 512 tokens of config 4
+# is printed by the test below and must stay under this, well inside the benchmark's 2e-2.
+CFG4_BF16_PREFILL_REL = 8e-3
+
+
+def test_cfg4_full_size_prefill_all_512_tokens(H, mixtral_layer, mixtral_experts_f64):
+    """Config 4 as stated: Mixtral-shaped layer, 512 tokens, router bias N(0,1).  Routing and
+    outputs are compared with the oracle for every token, through the batch call bench.py times."""
     cfg = synth.CONFIGS[4]
-    Wg, b, experts = synth.layer_weights(cfg)
+    _, (Wg, _, experts) = mixtral_layer                 # config 4's layer is config 2's plus a router bias
+    b = synth.router_bias(cfg)
     X = synth.tokens(cfg)
     T, k = cfg.n_tokens, cfg.top_k
     IDX = np.stack([O.route(Wg, b, X[t], k)[0] for t in range(T)])
@@ -188,20 +195,20 @@ def test_cfg4_full_size_prefill_sampled_tokens(H):
         x = H.to_device(X)
         idx, gate = st.route(0, x)
         assert np.array_equal(idx.cpu().numpy(), IDX)
-        y = st.ffn(0, idx, gate, x)
-        yn = H.from_device(y)
-        sample = [0, 1, 129, 300, 511]
-        for t in sample:
-            y_ref, _, _ = O.moe_layer(X[t], Wg, b, experts, k)
-            _check_tokens(yn, {t: y_ref}, [t])
-        # property that holds for every token: the grouped path agrees with the per-token GEMV path
-        worst = 0.0
-        for t0 in range(0, T, 8):
-            sl = slice(t0, t0 + 8)
-            y1 = H.from_device(st.ffn(0, idx[sl].contiguous(), gate[sl].contiguous(), x[sl].contiguous()))
-            a, r = O.widen(yn[sl]), O.widen(y1)
-            worst = max(worst, float(np.max(np.abs(a - r) / np.max(np.abs(r), axis=1, keepdims=True))))
-        assert worst <= 1e-2, worst
+        yn = H.from_device(st.ffn(0, idx, gate, x))
+        # a decode token on the same handle takes the GEMV path and agrees to one bf16 rounding
+        y1 = H.from_device(st.ffn(0, idx[7:8].contiguous(), gate[7:8].contiguous(), x[7:8].contiguous()))[0]
+    worst = 0.0
+    for t in range(T):
+        y_ref, idx_ref, _ = O.moe_layer(X[t], Wg, b, mixtral_experts_f64, k)
+        assert np.array_equal(idx_ref, IDX[t])
+        err = float(np.max(np.abs(O.widen(yn[t]) - y_ref)) / np.max(np.abs(y_ref)))
+        assert err <= BF16_REL, f"token {t}: {err}"
+        worst = max(worst, err)
+        if t == 7:
+            assert np.max(np.abs(O.widen(y1) - y_ref)) <= 1.5 * 2.0 ** -8 * np.max(np.abs(y_ref))
+    print("config 4: worst max-abs error over all 512 tokens = %.3e of max|y| (bf16 prefill path)" % worst)
+    assert worst <= CFG4_BF16_PREFILL_REL
 
 
 def test_cacheless_prefill_streams_each_expert_once_and_matches_resident(H):
