@@ -214,6 +214,30 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
                       const int32_t* predicted_idx_host, int32_t* idx_out_host,
                       odmoe_stats* stats);
 
+/*
+ * For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): odmoe_expert_ffn for experts resident in GPU-readable memory, token by
+ * token, without a handle and without any allocation by the library or the runtime:
+ *   y[t] = sum_i gate[t,i] * FFN_{idx[t,i]}(x[t]),  t = 0 .. n_tokens-1.
+ *   cfg              hidden, ffn, n_experts, top_k, dtype as for odmoe_layer_init; n_slots must be
+ *                    0; n_layers and glue are ignored.
+ *   expert_table_dev DEVICE array of n_experts pointers, each one expert buffer W1|W3|W2 in
+ *                    memory the GPU can read.
+ *   idx_dev[T,k], gate_dev[T,k], x_dev[T,H], y_dev[T,H]  device pointers, as for odmoe_expert_ffn
+ *                    (an idx entry outside [0, n_experts) selects nothing).
+ *   stream           hipStream_t the kernels are enqueued on (NULL = the null stream).
+ * The fp32 intermediate h[k, F] lives in a 1 MiB array that is part of the library's code object
+ * (each GPU the library runs on holds its own copy until the process ends), so
+ * top_k * ffn * 4 bytes must not exceed 1 MiB: larger shapes are refused with EINVAL and a
+ * message.  Output bits equal those of odmoe_expert_ffn's per-token path.  Asynchronous.  All
+ * calls on one GPU share that array: calls that may overlap (different streams, different host
+ * threads) race; calls on one stream are ordered and safe.  Nothing in it needs clearing between
+ * calls (every element a token reads was written for that token first).
+ */
+int odmoe_expert_ffn_static(const odmoe_config* cfg, const void* const* expert_table_dev,
+                            const int32_t* idx_dev, const float* gate_dev, const void* x_dev,
+                            int32_t n_tokens, void* y_dev, void* stream);
+
 /* Pinned host memory for the expert store (the workers' DRAM of Section 1). */
 int odmoe_pinned_alloc(uint64_t bytes, void** out_host);
 int odmoe_pinned_free(void* host);

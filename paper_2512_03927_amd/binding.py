@@ -21,7 +21,7 @@ ODMOE_MAX_EXPERTS = 1024
 # every symbol include/odmoe.h and include/odmoe_measure.h declare
 EXPORTS = (
     "odmoe_layer_init", "odmoe_layer_destroy", "odmoe_route_topk", "odmoe_expert_load_async",
-    "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_decode_step", "odmoe_pinned_alloc",
+    "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_expert_ffn_static", "odmoe_decode_step", "odmoe_pinned_alloc",
     "odmoe_pinned_free", "odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_probe_hbm",
     "odmoe_time_decode_kernels", "odmoe_time_expert_loads", "odmoe_load_window_ms", "odmoe_slot_groups",
 )
@@ -69,6 +69,7 @@ def lib() -> C.CDLL:
     L.odmoe_expert_evict.argtypes = [vp, i32, i32]
     L.odmoe_expert_ffn.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32]
     L.odmoe_decode_step.argtypes = [vp, vp, vp, vp, vp, C.POINTER(odmoe_stats)]
+    L.odmoe_expert_ffn_static.argtypes = [C.POINTER(odmoe_config), vp, vp, vp, vp, i32, vp, vp]
     L.odmoe_pinned_alloc.argtypes = [u64, C.POINTER(vp)]
     L.odmoe_pinned_free.argtypes = [vp]
     L.odmoe_probe_hbm.argtypes = [vp, vp, u64, i32, vp]
@@ -158,6 +159,12 @@ def odmoe_expert_ffn(h: int, layer: int, idx_dev, gate_dev, idx_host, x_dev, n_t
                      evict_after: int = 1) -> None:
     _check(lib().odmoe_expert_ffn(h, layer, _ptr(idx_dev), _ptr(gate_dev), _ptr(idx_host), _ptr(x_dev),
                                   n_tokens, _ptr(y_dev), evict_after))
+
+
+def odmoe_expert_ffn_static(cfg: odmoe_config, expert_table_dev, idx_dev, gate_dev, x_dev, n_tokens: int, y_dev,
+                            stream: Optional[int] = None) -> None:
+    _check(lib().odmoe_expert_ffn_static(C.byref(cfg), _ptr(expert_table_dev), _ptr(idx_dev), _ptr(gate_dev),
+                                         _ptr(x_dev), n_tokens, _ptr(y_dev), stream))
 
 
 def odmoe_decode_step(h: int, x_dev, y_dev, predicted_idx_host=None, idx_out_host=None,

@@ -231,6 +231,17 @@ void abandon_slots(odmoe_layer* h) {
   std::fill(h->done_pending.begin(), h->done_pending.end(), 0);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Device memory of the entry point that allocates nothing (odmoe_expert_ffn_static): the fp32
+// SwiGLU intermediate h[k, F] of one token.  Every GPU holds its own copy of the array for as long
+// as the process lives; host code never uses the array's name as an address, only the per-device
+// pointer hipGetSymbolAddress gives.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)1 << 20;
+constexpr int STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+void* g_scratch_ptr[STATIC_MAX_DEVICES];   // address of `scratch` on each device, once known
+
 }  // namespace
 
 extern "C" {
@@ -858,6 +869,49 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
   // a token that failed part-way leaves hinted and loaded experts in their slots: give them back
   if (rc != ODMOE_OK && rc != ODMOE_EINVAL) abandon_slots(h);
   return rc;
+}
+
+int odmoe_expert_ffn_static(const odmoe_config* cfg, const void* const* expert_table_dev,
+                            const int32_t* idx_dev, const float* gate_dev, const void* x_dev,
+                            int32_t n_tokens, void* y_dev, void* stream) {
+  int rc = validate_cfg(cfg);
+  if (rc) return rc;
+  if (cfg->n_slots != 0) return fail(ODMOE_EINVAL, "n_slots must be 0: the experts are read where the table points");
+  if (n_tokens < 0) return fail(ODMOE_EINVAL, "n_tokens %d < 0", n_tokens);
+  const size_t need = (size_t)cfg->top_k * cfg->ffn * sizeof(float);
+  if (need > STATIC_SCRATCH_BYTES)
+    return fail(ODMOE_EINVAL, "top_k * ffn = %d * %d floats (%zu bytes) exceed the %zu bytes of static scratch",
+                cfg->top_k, cfg->ffn, need, STATIC_SCRATCH_BYTES);
+  if (n_tokens == 0) return ODMOE_OK;
+  if (!expert_table_dev || !idx_dev || !gate_dev || !x_dev || !y_dev)
+    return fail(ODMOE_EINVAL, "table/idx/gate/x/y is NULL");
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return fail(ODMOE_EINVAL, "device %d out of range", dev);
+  void* hb = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (!hb) {
+    // first call on this device (it is the current one): where its copy of the array lives.  Two
+    // threads racing here get the same answer.
+    HIP_TRY(kernels_init());
+    HIP_TRY(hipGetSymbolAddress(&hb, HIP_SYMBOL(scratch)));
+    if (!hb) return fail(ODMOE_EHIP, "hipGetSymbolAddress gave no address");
+    __atomic_store_n(&g_scratch_ptr[dev], hb, __ATOMIC_RELEASE);
+  }
+  const Shape sh{cfg->hidden, cfg->ffn, cfg->n_experts, cfg->top_k, cfg->dtype};
+  ExpertSrc src{};
+  src.table = expert_table_dev;
+  src.table_off = 0;
+  src.n_experts = cfg->n_experts;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int k = cfg->top_k;
+  const size_t row = (size_t)cfg->hidden * dtype_size(cfg->dtype);
+  for (int t = 0; t < n_tokens; ++t) {
+    HIP_TRY(launch_ffn_up(s, sh, src, idx_dev + (size_t)t * k, static_cast<const char*>(x_dev) + t * row,
+                          static_cast<float*>(hb)));
+    HIP_TRY(launch_ffn_down(s, sh, src, idx_dev + (size_t)t * k, gate_dev + (size_t)t * k,
+                            static_cast<const float*>(hb), static_cast<char*>(y_dev) + t * row));
+  }
+  return ODMOE_OK;
 }
 
 }  // extern "C"
