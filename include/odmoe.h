@@ -36,6 +36,8 @@
  *     bf16 is the upper 16 bits of an fp32 (round-to-nearest-even).
  *   - One expert is ONE contiguous buffer:  W1[F,H] | W3[F,H] | W2[H,F]   (3*H*F elements).
  *   - hidden and ffn must be multiples of 8; 1 <= top_k <= min(n_experts, 8); n_experts <= 1024.
+ *   - Experts may instead be int8 codes with a scale per weight row (odmoe_config.expert_quant):
+ *     the quantised shadow model of Sections 1 and 3.2, which reads half the bytes per token.
  *   - The caller owns every buffer it passes in; weight buffers must outlive the handle.
  *     Streams are borrowed (never destroyed here).  The library owns its slot pool, scratch
  *     buffers, events and, if no copy stream was given, its copy streams.
@@ -78,6 +80,14 @@ typedef enum {
 
 typedef enum { ODMOE_F32 = 0, ODMOE_BF16 = 1 } odmoe_dtype;
 
+/* Weight quantisation of the shadow model (Sections 1, 3.2; the paper names FP16 / INT8 / NF4 and
+ * prints no scheme: these are the plain symmetric absmax ones, round half to even).
+ *   INT8_ROW  per weight row:  s = max|w| / 127,  q = clip(rne(w / s), -127, 127)
+ *   INT4_G64  per group of 64 consecutive weights of a row:  s = max|w| / 7,  q in -7..7
+ * Codes are stored offset-binary in one byte each: q + 128, resp. q + 8.  An all-zero row or
+ * group has scale 0 and codes of 0. */
+typedef enum { ODMOE_Q_NONE = 0, ODMOE_Q_INT8_ROW = 1, ODMOE_Q_INT4_G64 = 2 } odmoe_quant;
+
 #define ODMOE_MAX_TOPK 8
 #define ODMOE_MAX_EXPERTS 1024
 
@@ -91,6 +101,14 @@ typedef struct {
                         (any address the GPU can read will do, see "Experts read in place") */
   int32_t dtype;     /* odmoe_dtype */
   int32_t glue;      /* 0: x_{l+1} = y_l ; 1: x_{l+1} = rmsnorm(x_l + y_l) between stacked layers */
+  int32_t expert_quant; /* odmoe_quant of the expert buffers.  ODMOE_Q_NONE: weights in dtype.
+                        ODMOE_Q_INT8_ROW (a shadow model's experts): one expert is
+                          codes W1[F,H] | W3[F,H] | W2[H,F] (one byte each), then fp32 scales
+                          s1[F] | s3[F] | s2[H]
+                        as odmoe_quantize_expert writes it; x, y and the router stay in dtype, the
+                        GEMVs dequantise in registers and accumulate in fp32.  hidden and ffn must
+                        be multiples of 16, hidden <= 8192, and batches run token by token (no
+                        grouped GEMM).  ODMOE_Q_INT4_G64 is not an expert format. */
 } odmoe_config;
 
 typedef struct {
@@ -237,6 +255,47 @@ int odmoe_decode_step(odmoe_layer_t* h, const void* x_dev, void* y_dev,
 int odmoe_expert_ffn_static(const odmoe_config* cfg, const void* const* expert_table_dev,
                             const int32_t* idx_dev, const float* gate_dev, const void* x_dev,
                             int32_t n_tokens, void* y_dev, void* stream);
+
+/* Bytes of one expert buffer as a handle made from cfg expects it: 3*H*F elements of dtype, or for
+ * ODMOE_Q_INT8_ROW 3*H*F code bytes + 4*(2*F + H) bytes of scales.  0 for a NULL or invalid cfg. */
+uint64_t odmoe_expert_bytes(const odmoe_config* cfg);
+
+/*
+ * The shadow model's weights (Sections 1, 3.2): quantise w_dev[rows, cols] (row-major, dtype) on
+ * the device.  kind: ODMOE_Q_INT8_ROW or ODMOE_Q_INT4_G64 (cols a multiple of 64).  Outputs, each
+ * optional (NULL = not wanted), all device pointers:
+ *   code_dev     uint8 [rows, cols], offset-binary codes
+ *   scale_dev    fp32 [rows] (INT8_ROW) or [rows, cols/64] (INT4_G64): the float64 scale rounded once
+ *   dequant_dev  [rows, cols] in dtype: q * scale (float64) rounded once to dtype -- the weights a
+ *                shadow copy held in the storage dtype uses
+ * The scale, the division and the rounding are done in float64, so every code equals the one a
+ * float64 CPU computation of the formulas above gives.  Asynchronous on `stream`.
+ */
+int odmoe_quantize(const void* w_dev, int32_t dtype, int64_t rows, int64_t cols, int32_t kind,
+                   uint8_t* code_dev, float* scale_dev, void* dequant_dev, void* stream);
+
+/* One stored expert W1[F,H] | W3[F,H] | W2[H,F] (cfg->dtype, device) into the ODMOE_Q_INT8_ROW
+ * expert buffer described at odmoe_config (dst_dev: odmoe_expert_bytes of the quantised config,
+ * device).  cfg->expert_quant is ignored.  Asynchronous on `stream`. */
+int odmoe_quantize_expert(const odmoe_config* cfg, const void* expert_dev, void* dst_dev, void* stream);
+
+/*
+ * Scaled emulative prediction, emulated on one GPU (Sections 1, 3.2): `shadow` (a stack of the
+ * same shape as `main`, normally with quantised weights, resident) decodes each token first, its
+ * expert selection is handed to `main` as the prediction, `main` decodes the same token, and the
+ * fraction of main's activated experts that were predicted is the token's recall (Section 3.2).
+ * There is no attention or KV cache in this library, so an autoregressive iteration is emulated by
+ * feeding main's output back as its next input.  aligned != 0: the shadow starts every iteration
+ * from main's input (the token / KV alignment of Section 3.2, every iteration); aligned == 0: it
+ * follows its own outputs after the first iteration.
+ *   x0_dev [H] first input; recall_out host float[n_iter]; x_final_dev [H] or NULL receives main's
+ *   last output; shadow_ms / main_ms (host, may be NULL) receive the wall time spent in each
+ *   stack's decode steps.  Predictions change main's timing only, never its output.  Blocks;
+ *   allocates and frees small device buffers.
+ */
+int odmoe_sep_emulate(odmoe_layer_t* main_stack, odmoe_layer_t* shadow, const void* x0_dev,
+                      int32_t n_iter, int32_t aligned, float* recall_out, void* x_final_dev,
+                      float* shadow_ms, float* main_ms);
 
 /* Pinned host memory for the expert store (the workers' DRAM of Section 1). */
 int odmoe_pinned_alloc(uint64_t bytes, void** out_host);

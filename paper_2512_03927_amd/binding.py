@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libodmoe.so")
 
 ODMOE_OK, ODMOE_EINVAL, ODMOE_ENOMEM, ODMOE_EHIP, ODMOE_ESTATE, ODMOE_EBUSY = 0, -1, -2, -3, -4, -5
 ODMOE_F32, ODMOE_BF16 = 0, 1
+ODMOE_Q_NONE, ODMOE_Q_INT8_ROW, ODMOE_Q_INT4_G64 = 0, 1, 2
 ODMOE_MAX_TOPK = 8
 ODMOE_MAX_EXPERTS = 1024
 
@@ -24,12 +25,13 @@ EXPORTS = (
     "odmoe_expert_evict", "odmoe_expert_ffn", "odmoe_expert_ffn_static", "odmoe_decode_step", "odmoe_pinned_alloc",
     "odmoe_pinned_free", "odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_probe_hbm",
     "odmoe_time_decode_kernels", "odmoe_time_expert_loads", "odmoe_load_window_ms", "odmoe_slot_groups",
+    "odmoe_expert_bytes", "odmoe_quantize", "odmoe_quantize_expert", "odmoe_sep_emulate",
 )
 
 
 class odmoe_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
-                ("hidden", "ffn", "n_experts", "top_k", "n_layers", "n_slots", "dtype", "glue")]
+                ("hidden", "ffn", "n_experts", "top_k", "n_layers", "n_slots", "dtype", "glue", "expert_quant")]
 
 
 class odmoe_stats(C.Structure):
@@ -70,6 +72,12 @@ def lib() -> C.CDLL:
     L.odmoe_expert_ffn.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32]
     L.odmoe_decode_step.argtypes = [vp, vp, vp, vp, vp, C.POINTER(odmoe_stats)]
     L.odmoe_expert_ffn_static.argtypes = [C.POINTER(odmoe_config), vp, vp, vp, vp, i32, vp, vp]
+    L.odmoe_expert_bytes.argtypes = [C.POINTER(odmoe_config)]
+    L.odmoe_expert_bytes.restype = u64
+    L.odmoe_quantize.argtypes = [vp, i32, C.c_int64, C.c_int64, i32, vp, vp, vp, vp]
+    L.odmoe_quantize_expert.argtypes = [C.POINTER(odmoe_config), vp, vp, vp]
+    L.odmoe_sep_emulate.argtypes = [vp, vp, vp, i32, i32, C.POINTER(C.c_float), vp, C.POINTER(C.c_float),
+                                    C.POINTER(C.c_float)]
     L.odmoe_pinned_alloc.argtypes = [u64, C.POINTER(vp)]
     L.odmoe_pinned_free.argtypes = [vp]
     L.odmoe_probe_hbm.argtypes = [vp, vp, u64, i32, vp]
@@ -86,7 +94,7 @@ def lib() -> C.CDLL:
     L.odmoe_version.restype = C.c_char_p
     for name in EXPORTS:
         if name not in ("odmoe_slot_pool_bytes", "odmoe_last_error", "odmoe_version", "odmoe_load_window_ms",
-                        "odmoe_slot_groups"):
+                        "odmoe_slot_groups", "odmoe_expert_bytes"):
             getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -171,6 +179,29 @@ def odmoe_decode_step(h: int, x_dev, y_dev, predicted_idx_host=None, idx_out_hos
                       stats: Optional[odmoe_stats] = None) -> None:
     _check(lib().odmoe_decode_step(h, _ptr(x_dev), _ptr(y_dev), _ptr(predicted_idx_host),
                                    _ptr(idx_out_host), C.byref(stats) if stats is not None else None))
+
+
+def odmoe_expert_bytes(cfg: odmoe_config) -> int:
+    return int(lib().odmoe_expert_bytes(C.byref(cfg)))
+
+
+def odmoe_quantize(w_dev, dtype: int, rows: int, cols: int, kind: int, code_dev=None, scale_dev=None,
+                   dequant_dev=None, stream: Optional[int] = None) -> None:
+    _check(lib().odmoe_quantize(_ptr(w_dev), dtype, rows, cols, kind, _ptr(code_dev), _ptr(scale_dev),
+                                _ptr(dequant_dev), stream))
+
+
+def odmoe_quantize_expert(cfg: odmoe_config, expert_dev, dst_dev, stream: Optional[int] = None) -> None:
+    _check(lib().odmoe_quantize_expert(C.byref(cfg), _ptr(expert_dev), _ptr(dst_dev), stream))
+
+
+def odmoe_sep_emulate(main: int, shadow: int, x0_dev, n_iter: int, aligned: bool, x_final_dev=None):
+    """(recall per iteration: list of float, shadow_ms, main_ms)."""
+    rec = (C.c_float * max(1, n_iter))()
+    sm, mm = C.c_float(), C.c_float()
+    _check(lib().odmoe_sep_emulate(main, shadow, _ptr(x0_dev), n_iter, 1 if aligned else 0, rec, _ptr(x_final_dev),
+                                   C.byref(sm), C.byref(mm)))
+    return [float(rec[i]) for i in range(n_iter)], sm.value, mm.value
 
 
 def odmoe_pinned_alloc(nbytes: int) -> int:

@@ -49,8 +49,9 @@ int main(int argc, char** argv) {
   }
   FILE* in = fopen(argv[1], "rb");
   if (!in) { perror(argv[1]); return 1; }
-  odmoe_config cfg;
-  if (!read_exact(in, &cfg, sizeof cfg)) { fprintf(stderr, "short header\n"); return 1; }
+  int32_t hdr[8];
+  if (!read_exact(in, hdr, sizeof hdr)) { fprintf(stderr, "short header\n"); return 1; }
+  odmoe_config cfg = {hdr[0], hdr[1], hdr[2], hdr[3], hdr[4], hdr[5], hdr[6], hdr[7], ODMOE_Q_NONE};
   const int L = cfg.n_layers, E = cfg.n_experts, k = cfg.top_k;
   const size_t es = cfg.dtype == ODMOE_F32 ? 4 : 2;
   const size_t router_bytes = (size_t)E * cfg.hidden * es;

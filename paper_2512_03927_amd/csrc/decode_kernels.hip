@@ -5,85 +5,12 @@
 // read exactly once per token), so they stream the weights with 128-bit non-temporal loads,
 // keep the input vector slice in registers (in LDS for shapes too large for that) and never
 // touch the matrix cores.
-#include "kernels.h"
+#include "gemv_common.hpp"
 
 #include <cstdlib>
 
 namespace odmoe {
 namespace {
-
-constexpr int WAVE = 64;
-typedef uint16_t bf16_t;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-
-// fp32 -> bf16, round to nearest even (finite values).
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
-
-template <typename T>
-struct DT;
-template <>
-struct DT<float> {
-  static constexpr int VEC = 4;  // elements per 128-bit load
-  static __device__ __forceinline__ void unpack(u32x4 q, float* f) {
-    f[0] = __uint_as_float(q.x); f[1] = __uint_as_float(q.y);
-    f[2] = __uint_as_float(q.z); f[3] = __uint_as_float(q.w);
-  }
-  static __device__ __forceinline__ float to_f32(float v) { return v; }
-  static __device__ __forceinline__ float from_f32(float v) { return v; }
-};
-template <>
-struct DT<bf16_t> {
-  static constexpr int VEC = 8;
-  static __device__ __forceinline__ void unpack(u32x4 q, float* f) {
-    f[0] = bf16_lo(q.x); f[1] = bf16_hi(q.x); f[2] = bf16_lo(q.y); f[3] = bf16_hi(q.y);
-    f[4] = bf16_lo(q.z); f[5] = bf16_hi(q.z); f[6] = bf16_lo(q.w); f[7] = bf16_hi(q.w);
-  }
-  static __device__ __forceinline__ float to_f32(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
-  static __device__ __forceinline__ bf16_t from_f32(float v) { return f32_to_bf16(v); }
-};
-
-template <typename T>
-__device__ __forceinline__ u32x4 load16(const T* p) {
-  return *reinterpret_cast<const u32x4*>(p);
-}
-// Streaming load for weights: each byte is used once, keep it out of the way of reused lines.
-// Expert pointers reach the kernels through a struct or a table, so the compiler cannot tell
-// that they are global addresses; the explicit address-space cast turns what would be flat
-// loads into global loads.
-typedef const __attribute__((address_space(1))) u32x4* global_u32x4_ptr;
-template <typename T>
-__device__ __forceinline__ u32x4 load16_stream(const T* p) {
-  return __builtin_nontemporal_load((global_u32x4_ptr)(p));
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
-  return v;
-}
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
-  return v;
-}
-
-// Base address of the expert of rank i, or null when idx[i] is not an expert id (ids reach the
-// table path from the caller's device memory, which the host cannot check without blocking):
-// such a rank is left out of the sum, as in the grouped path.  The answer is wave-uniform.
-__device__ __forceinline__ const void* expert_ptr(const ExpertSrc& s, const int32_t* idx, int i) {
-  if (s.resolved) return s.resolved[i];
-  if (!s.table) return s.slot[i];
-  const uint32_t e = (uint32_t)idx[i];
-  return e < (uint32_t)s.n_experts ? s.table[s.table_off + e] : nullptr;
-}
 
 // ---------------------------------------------------------------------------------------------
 // LDS layout of an fp32 vector that 128-bit weight loads are multiplied with.  Vector element
@@ -337,7 +264,6 @@ __global__ __launch_bounds__(256) void ffn_up_kernel(ExpertSrc src, const int32_
     if (r >= total) break;
     const int i = (int)(r / F), j = (int)(r % F);
     const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
-    if (!base) continue;   // not an expert id: the w2 kernel skips this rank too
     const T* w1 = base + (size_t)j * H;
     const T* w3 = base + (size_t)F * H + (size_t)j * H;
     float a, b;
@@ -364,13 +290,12 @@ __global__ __launch_bounds__(512) void ffn_down_kernel(ExpertSrc src, const int3
 #pragma unroll
   for (int rr = 0; rr < RPW; ++rr) acc[rr] = 0.f;
   for (int i = 0; i < k; ++i) {
-    const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
-    if (!base) continue;   // the same for every thread of the block
+    bool ok;
+    const T* w2 = static_cast<const T*>(expert_ptr(src, idx, i, &ok)) + (size_t)2 * F * H;
     __syncthreads();
     stage_vec<float, VEC>(hbuf + (size_t)i * F, svec, F);
     __syncthreads();
-    const float g = gate[i];
-    const T* w2 = base + (size_t)2 * F * H;
+    const float g = ok ? gate[i] : 0.f;   // an idx entry that is no expert id adds nothing
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
       const int r = r0 + rr;
@@ -506,7 +431,6 @@ __global__ __launch_bounds__(256) void ffn_up_reg_kernel(ExpertSrc src, const in
     const int seg_end = ((i + 1) * F < r_end) ? (i + 1) * F : r_end;
     const int nrow = seg_end - r;
     const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
-    if (!base) { r = seg_end; continue; }   // not an expert id: the w2 kernel skips this rank too
     float* hout = hbuf + (size_t)i * F + j0;
     // Two row pairs alternate between two register sets: the loads of the next pair are on their
     // way while the current one is multiplied and reduced, so the wave (one per SIMD) always has
@@ -585,10 +509,9 @@ __global__ __launch_bounds__(CPW <= 4 ? 1024 : 512) void ffn_down_reg_kernel(Exp
     off[c] = (v < nvec ? v : nvec - 1) * VEC;
   }
   for (int i = eg; i < k; i += n_eg) {
-    const float g = gate[i];
-    const T* base = static_cast<const T*>(expert_ptr(src, idx, i));
-    if (!base) continue;
-    const T* w2 = base + (size_t)2 * F * H;
+    bool ok;
+    const T* w2 = static_cast<const T*>(expert_ptr(src, idx, i, &ok)) + (size_t)2 * F * H;
+    const float g = ok ? gate[i] : 0.f;   // an idx entry that is no expert id adds nothing
     const float* hv = hbuf + (size_t)i * F;
     float hr[CPW][VEC];
 #pragma unroll
@@ -637,23 +560,29 @@ constexpr size_t MAX_LDS = 160 * 1024;
 
 }  // namespace
 
-namespace {
-// Launch-shape overrides for tuning sweeps, compiled in only with -DODMOE_TUNING (never in the
-// library that ships: the expert-group count changes the order of fp32 additions).  0 = the
-// built-in policy.  Read once from the environment: ODMOE_TUNE_UP_RPW (rows per wave of the w1/w3
-// GEMV), ODMOE_TUNE_DOWN_RPB (rows per block of the w2 GEMV), ODMOE_TUNE_DOWN_EG (its expert
-// groups per block), ODMOE_TUNE_ROUTE_SPLIT_E (fewest experts for the multi-block router).
 #ifdef ODMOE_TUNING
-int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0, g_tune_route_split_e = 0;
+int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0, g_tune_route_split_e = 0, g_tune_q8_rif = 0;
+namespace {
 int env_int(const char* name) {
   const char* v = getenv(name);
   const int n = v ? atoi(v) : 0;
   return n > 0 ? n : 0;
 }
-#else
-constexpr int g_tune_up_rpw = 0, g_tune_down_rpb = 0, g_tune_down_eg = 0, g_tune_route_split_e = 0;
-#endif
 }  // namespace
+#endif
+
+int num_cu() {
+  static int n_cached = 0;
+  if (n_cached == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      n_cached = n;
+    else
+      n_cached = 256;
+  }
+  return n_cached;
+}
 
 hipError_t kernels_init() {
 #ifdef ODMOE_TUNING
@@ -661,6 +590,7 @@ hipError_t kernels_init() {
   g_tune_route_split_e = env_int("ODMOE_TUNE_ROUTE_SPLIT_E");
   g_tune_down_rpb = env_int("ODMOE_TUNE_DOWN_RPB");
   g_tune_down_eg = env_int("ODMOE_TUNE_DOWN_EG");
+  g_tune_q8_rif = env_int("ODMOE_TUNE_Q8_RIF");
 #endif
   hipError_t e;
   const int big = (int)MAX_LDS;
@@ -712,19 +642,6 @@ hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, con
 namespace {
 
 
-int g_num_cu = 0;
-int num_cu() {
-  if (g_num_cu == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      g_num_cu = n;
-    else
-      g_num_cu = 256;
-  }
-  return g_num_cu;
-}
-
 template <typename T, int NCH>
 hipError_t launch_up_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
                            const void* x, float* hbuf) {
@@ -768,48 +685,14 @@ hipError_t launch_up_reg(hipStream_t s, const Shape& sh, const ExpertSrc& src, c
 template <typename T, int CPW>
 hipError_t launch_down_reg_n(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
                              const float* gate, const float* hbuf, void* y, int nwb) {
-  // expert groups: waves left over in a block (up to 8 when slices are short) take different experts
-  const int max_waves = CPW <= 4 ? 16 : 8;
-  int n_eg = 1;
-  if (nwb <= 2) n_eg = sh.k < max_waves / nwb ? sh.k : max_waves / nwb;
-  else if (nwb <= 4) n_eg = sh.k < 2 ? sh.k : 2;   // blocks of at least 6 waves keep enough loads in flight
-  if (n_eg > 8) n_eg = 8;
-  if (g_tune_down_eg > 0) n_eg = g_tune_down_eg;
-  if (n_eg > max_waves / nwb) n_eg = max_waves / nwb;   // block size limit of the kernel
-  if (n_eg > sh.k) n_eg = sh.k;
-  if (n_eg < 1) n_eg = 1;
-  int rpb = (sh.H + num_cu() - 1) / num_cu();
-  if (n_eg > 1 && nwb <= 2 && rpb > 4) rpb = 4;  // small layers: more, shorter blocks
-  rpb = (rpb + 1) & ~1;              // two rows in flight
-  // Across the host link: fewer blocks with longer runs.  The expert groups stay as they are, so
-  // that the order of the fp32 additions, and with it every output bit, is that of experts in HBM.
-  if (rpb > 64 || sh.host_link) rpb = 64;
-  if (g_tune_down_rpb > 0) rpb = (g_tune_down_rpb + 1) & ~1;
+  int n_eg, rpb;
+  down_block_shape(sh, CPW, nwb, g_tune_down_eg, g_tune_down_rpb, &n_eg, &rpb);
   const int grid = (sh.H + rpb - 1) / rpb;
   const int nw = nwb * n_eg;
   const size_t lds = (size_t)nw * rpb * sizeof(float);
   ffn_down_reg_kernel<T, CPW><<<grid, nw * WAVE, lds, s>>>(src, idx, gate, hbuf, static_cast<T*>(y),
                                                            sh.H, sh.F, sh.k, rpb, nwb);
   return hipGetLastError();
-}
-
-// Split of the NC column chunks of a w2 row over the waves of a block: CPW chunks per wave.
-// Up to 4 chunks per wave (blocks of up to 16 waves) with the least padding, ties going to
-// more chunks per wave; rows too long for that take 5..8 chunks per wave (up to 8 waves).
-inline bool pick_down_split(int nc, int* cpw_out, int* nwb_out) {
-  int best_cpw = 0, best_waste = 1 << 30;
-  for (int cpw = 1; cpw <= 4; ++cpw) {
-    const int nwb = (nc + cpw - 1) / cpw;
-    if (nwb > 16) continue;
-    const int waste = nwb * cpw - nc;
-    if (waste <= best_waste) { best_waste = waste; best_cpw = cpw; }
-  }
-  for (int cpw = 5; cpw <= 8 && !best_cpw; ++cpw)
-    if ((nc + cpw - 1) / cpw <= 8) best_cpw = cpw;
-  if (!best_cpw) return false;
-  *cpw_out = best_cpw;
-  *nwb_out = (nc + best_cpw - 1) / best_cpw;
-  return true;
 }
 
 template <typename T>
@@ -828,6 +711,7 @@ hipError_t launch_down_reg(hipStream_t s, const Shape& sh, const ExpertSrc& src,
 
 hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
                          const void* x, float* hbuf) {
+  if (sh.quant == ODMOE_Q_INT8_ROW) return launch_ffn_up_q8(s, sh, src, idx, x, hbuf);
   const int vec = sh.dtype == ODMOE_F32 ? 4 : 8;
   const int nch = (sh.H + WAVE * vec - 1) / (WAVE * vec);
   if (nch <= 16) {
@@ -851,6 +735,7 @@ hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, c
 
 hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
                            const int32_t* idx, const float* gate, const float* hbuf, void* y) {
+  if (sh.quant == ODMOE_Q_INT8_ROW) return launch_ffn_down_q8(s, sh, src, idx, gate, hbuf, y);
   const int vec = sh.dtype == ODMOE_F32 ? 4 : 8;
   const int nc = (sh.F + WAVE * vec - 1) / (WAVE * vec);
   int cpw = 0, nwb = 0;

@@ -11,7 +11,7 @@ namespace odmoe {
 // Where the weights of the i-th selected expert (rank i in idx) live.
 //   resolved : resolved != nullptr, pointer = resolved[i]   (device array the router kernel filled)
 //   resident : table != nullptr, pointer = table[table_off + idx[i]]   (device table, L*E entries);
-//              idx[i] outside [0, n_experts) selects nothing: that rank adds nothing to y
+//              idx[i] outside [0, n_experts) selects nothing: that rank gets gate weight 0
 //   cacheless: otherwise, pointer = slot[i]                            (HBM slot bases by rank)
 struct ExpertSrc {
   const void* slot[ODMOE_MAX_TOPK];
@@ -28,6 +28,9 @@ struct Shape {
   // saturated by about a hundred waves that each stream a long contiguous run; thousands of short
   // runs lose 4-7 % of its rate.
   int32_t host_link = 0;
+  // odmoe_quant of the expert buffers: 0 = weights in `dtype`; ODMOE_Q_INT8_ROW = int8 codes with
+  // one fp32 scale per weight row (x, y and the router stay in `dtype`).
+  int32_t quant = 0;
 };
 
 // Device scratch that lets the router spread one token over several blocks: logits
@@ -57,6 +60,20 @@ hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, c
 // y = sum_i gate[i] * (W2_i h_i) for ONE token; y in sh.dtype [H].
 hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
                            const int32_t* idx, const float* gate, const float* hbuf, void* y);
+
+// The same two GEMVs over int8 expert buffers (codes W1 | W3 | W2 offset-binary, then fp32 scales
+// s1[F] | s3[F] | s2[H]); launch_ffn_up / launch_ffn_down forward here when sh.quant says so.
+bool q8_supported(const Shape& sh);   // H and F multiples of 16, H <= 8192
+hipError_t launch_ffn_up_q8(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                            const void* x, float* hbuf);
+hipError_t launch_ffn_down_q8(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                              const float* gate, const float* hbuf, void* y);
+
+// Symmetric absmax quantisation of w[rows, cols] (dtype) on the device; kind is an odmoe_quant.
+// code (u8, offset-binary), scale (fp32, per row or per group of 64) and deq (code * scale rounded
+// once to dtype) may each be null.
+hipError_t launch_quantize(hipStream_t s, const void* w, int32_t dtype, int64_t rows, int64_t cols,
+                           int32_t kind, uint8_t* code, float* scale, void* deq);
 
 // glue = 1: x_next = rmsnorm(x + y) (eps 1e-6).  All [H] in sh.dtype.
 hipError_t launch_glue(hipStream_t s, const Shape& sh, const void* x, const void* y, void* x_next);

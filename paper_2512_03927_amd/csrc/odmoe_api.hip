@@ -54,6 +54,12 @@ int guarded(F&& body) noexcept {
 
 size_t dtype_size(int32_t dt) { return dt == ODMOE_F32 ? 4 : 2; }
 
+size_t expert_bytes_of(const odmoe_config& c) {
+  const size_t hf = (size_t)c.hidden * c.ffn;
+  if (c.expert_quant == ODMOE_Q_INT8_ROW) return 3 * hf + sizeof(float) * (2 * (size_t)c.ffn + c.hidden);
+  return 3 * hf * dtype_size(c.dtype);
+}
+
 }  // namespace
 
 struct odmoe_layer {
@@ -115,6 +121,11 @@ int validate_cfg(const odmoe_config* c) {
     return fail(ODMOE_EINVAL, "n_slots %d must be 0 (resident) or >= top_k", c->n_slots);
   if (c->dtype != ODMOE_F32 && c->dtype != ODMOE_BF16) return fail(ODMOE_EINVAL, "bad dtype %d", c->dtype);
   if (c->glue != 0 && c->glue != 1) return fail(ODMOE_EINVAL, "bad glue %d", c->glue);
+  if (c->expert_quant != ODMOE_Q_NONE && c->expert_quant != ODMOE_Q_INT8_ROW)
+    return fail(ODMOE_EINVAL, "expert_quant %d: experts are stored in dtype (0) or as int8 rows (1)", c->expert_quant);
+  if (c->expert_quant == ODMOE_Q_INT8_ROW && (c->hidden % 16 || c->ffn % 16 || c->hidden > 8192))
+    return fail(ODMOE_EINVAL, "int8 experts need hidden (%d) and ffn (%d) to be multiples of 16 and hidden <= 8192",
+                c->hidden, c->ffn);
   // the GEMV kernels keep one fp32 input vector in LDS (160 KB per workgroup on gfx950)
   const long max_vec = 160 * 1024 / 4;
   const long chunk = c->dtype == ODMOE_F32 ? 256 : 512;
@@ -248,6 +259,43 @@ extern "C" {
 
 const char* odmoe_last_error(void) { return g_err; }
 const char* odmoe_version(void) { return "odmoe 0.1 (gfx950)"; }
+
+uint64_t odmoe_expert_bytes(const odmoe_config* cfg) {
+  if (!cfg || validate_cfg(cfg) != ODMOE_OK) return 0;
+  return expert_bytes_of(*cfg);
+}
+
+int odmoe_quantize(const void* w_dev, int32_t dtype, int64_t rows, int64_t cols, int32_t kind,
+                   uint8_t* code_dev, float* scale_dev, void* dequant_dev, void* stream) {
+  if (!w_dev) return fail(ODMOE_EINVAL, "w is NULL");
+  if (dtype != ODMOE_F32 && dtype != ODMOE_BF16) return fail(ODMOE_EINVAL, "bad dtype %d", dtype);
+  if (rows < 0 || cols < 0) return fail(ODMOE_EINVAL, "rows / cols negative");
+  if (kind != ODMOE_Q_INT8_ROW && kind != ODMOE_Q_INT4_G64) return fail(ODMOE_EINVAL, "bad quantisation kind %d", kind);
+  if (kind == ODMOE_Q_INT4_G64 && cols % 64) return fail(ODMOE_EINVAL, "cols (%lld) must be a multiple of 64", (long long)cols);
+  if (rows > 0x7fffffffLL) return fail(ODMOE_EINVAL, "too many rows");
+  HIP_TRY(launch_quantize(static_cast<hipStream_t>(stream), w_dev, dtype, rows, cols, kind, code_dev, scale_dev,
+                          dequant_dev));
+  return ODMOE_OK;
+}
+
+int odmoe_quantize_expert(const odmoe_config* cfg, const void* expert_dev, void* dst_dev, void* stream) {
+  if (!cfg) return fail(ODMOE_EINVAL, "cfg is NULL");
+  odmoe_config qc = *cfg;
+  qc.expert_quant = ODMOE_Q_INT8_ROW;
+  int rc = validate_cfg(&qc);
+  if (rc) return rc;
+  if (!expert_dev || !dst_dev) return fail(ODMOE_EINVAL, "expert / dst is NULL");
+  const size_t H = cfg->hidden, F = cfg->ffn, hf = H * F, es = dtype_size(cfg->dtype);
+  const char* src = static_cast<const char*>(expert_dev);
+  uint8_t* code = static_cast<uint8_t*>(dst_dev);
+  float* scale = reinterpret_cast<float*>(code + 3 * hf);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(launch_quantize(s, src, cfg->dtype, F, H, ODMOE_Q_INT8_ROW, code, scale, nullptr));                       // W1
+  HIP_TRY(launch_quantize(s, src + hf * es, cfg->dtype, F, H, ODMOE_Q_INT8_ROW, code + hf, scale + F, nullptr));    // W3
+  HIP_TRY(launch_quantize(s, src + 2 * hf * es, cfg->dtype, H, F, ODMOE_Q_INT8_ROW, code + 2 * hf, scale + 2 * F,
+                          nullptr));                                                                                   // W2
+  return ODMOE_OK;
+}
 
 int odmoe_pinned_alloc(uint64_t bytes, void** out_host) {
   if (!out_host || bytes == 0) return fail(ODMOE_EINVAL, "bad arguments");
@@ -395,8 +443,9 @@ static int layer_init_impl(const odmoe_config* cfg, const void* const* router_w,
   *made = h;
   h->cfg = *cfg;
   h->sh = Shape{cfg->hidden, cfg->ffn, E, k, cfg->dtype};
+  h->sh.quant = cfg->expert_quant;
   h->esize = dtype_size(cfg->dtype);
-  h->expert_bytes = (size_t)3 * cfg->hidden * cfg->ffn * h->esize;
+  h->expert_bytes = expert_bytes_of(*cfg);
   h->compute = static_cast<hipStream_t>(compute_stream);
   h->router_w.assign(router_w, router_w + L);
   h->router_b.assign(L, nullptr);
@@ -597,7 +646,7 @@ static int expert_ffn_impl(odmoe_layer_t* h, int32_t layer, const int32_t* idx_d
     src.n_experts = E;
     // Tokens grouped by expert read each expert once; token by token reads k experts per token:
     // grouping pays as soon as the token-slots outnumber the experts (and always from 16 tokens).
-    if ((n_tokens >= 16 || (int64_t)n_tokens * k > E) && prefill_supported(h->sh)) {
+    if ((n_tokens >= 16 || (int64_t)n_tokens * k > E) && prefill_supported(h->sh) && !h->sh.quant) {
       if ((rc = ensure_prefill_ws(h, n_tokens))) return rc;
       HIP_TRY(launch_prefill(h->compute, h->sh, h->table_dev, layer * E, idx_dev, gate_dev, x_dev,
                              n_tokens, y_dev, h->prefill_ws, h->prefill_ws_bytes));
@@ -616,8 +665,8 @@ static int expert_ffn_impl(odmoe_layer_t* h, int32_t layer, const int32_t* idx_d
   // copy has landed, and the slot is handed to the next expert: with S >= 2 slots the copy of
   // the next expert overlaps the GEMMs of the current one.
   if (n_tokens >= 2) {
-    if (!prefill_supported(h->sh))
-      return fail(ODMOE_EINVAL, "cacheless batches need hidden and ffn to be multiples of 64");
+    if (!prefill_supported(h->sh) || h->sh.quant)
+      return fail(ODMOE_EINVAL, "cacheless batches need hidden and ffn to be multiples of 64 and experts stored in dtype");
     if ((rc = ensure_prefill_ws(h, n_tokens))) return rc;
     const size_t n = (size_t)n_tokens * k;
     std::vector<int32_t> ids_all(n);
@@ -897,7 +946,8 @@ int odmoe_expert_ffn_static(const odmoe_config* cfg, const void* const* expert_t
     if (!hb) return fail(ODMOE_EHIP, "hipGetSymbolAddress gave no address");
     __atomic_store_n(&g_scratch_ptr[dev], hb, __ATOMIC_RELEASE);
   }
-  const Shape sh{cfg->hidden, cfg->ffn, cfg->n_experts, cfg->top_k, cfg->dtype};
+  Shape sh{cfg->hidden, cfg->ffn, cfg->n_experts, cfg->top_k, cfg->dtype};
+  sh.quant = cfg->expert_quant;
   ExpertSrc src{};
   src.table = expert_table_dev;
   src.table_off = 0;
@@ -912,6 +962,75 @@ int odmoe_expert_ffn_static(const odmoe_config* cfg, const void* const* expert_t
                             static_cast<const float*>(hb), static_cast<char*>(y_dev) + t * row));
   }
   return ODMOE_OK;
+}
+
+static int sep_emulate_impl(odmoe_layer_t* main_stack, odmoe_layer_t* shadow, const void* x0_dev, int32_t n_iter,
+                            int32_t aligned, float* recall_out, void* x_final_dev, float* shadow_ms,
+                            float* main_ms) {
+  if (!main_stack || !shadow) return fail(ODMOE_EINVAL, "handle is NULL");
+  if (!x0_dev || !recall_out || n_iter < 0) return fail(ODMOE_EINVAL, "bad arguments");
+  const odmoe_config &m = main_stack->cfg, &q = shadow->cfg;
+  if (m.hidden != q.hidden || m.n_layers != q.n_layers || m.top_k != q.top_k || m.n_experts != q.n_experts ||
+      m.dtype != q.dtype)
+    return fail(ODMOE_EINVAL, "the shadow stack must have the main stack's hidden size, layers, experts, top_k and dtype");
+  if (shadow->pool) return fail(ODMOE_EINVAL, "the shadow stack must be resident (n_slots = 0)");
+  const int L = m.n_layers, k = m.top_k;
+  const size_t row = (size_t)m.hidden * main_stack->esize;
+  char* buf = nullptr;   // four state vectors: main in / out, shadow in / out
+  HIP_TRY(hipMalloc((void**)&buf, 4 * row));
+  std::vector<int32_t> pred((size_t)L * k), used((size_t)L * k);
+  using clk = std::chrono::steady_clock;
+  double t_shadow = 0.0, t_main = 0.0;
+  int rc = ODMOE_OK;
+  auto body = [&]() -> int {
+    char *xm = buf, *ym = buf + row, *xs = buf + 2 * row, *ys = buf + 3 * row;
+    HIP_TRY(hipMemcpyAsync(xm, x0_dev, row, hipMemcpyDeviceToDevice, main_stack->compute));
+    HIP_TRY(hipStreamSynchronize(main_stack->compute));
+    for (int it = 0; it < n_iter; ++it) {
+      const bool from_main = aligned || it == 0;
+      auto t0 = clk::now();
+      if ((rc = odmoe_decode_step(shadow, from_main ? xm : xs, ys, nullptr, pred.data(), nullptr))) return rc;
+      auto t1 = clk::now();
+      odmoe_stats st{};
+      if ((rc = odmoe_decode_step(main_stack, xm, ym, pred.data(), used.data(), &st))) return rc;
+      auto t2 = clk::now();
+      t_shadow += std::chrono::duration<double, std::milli>(t1 - t0).count();
+      t_main += std::chrono::duration<double, std::milli>(t2 - t1).count();
+      // recall of this token (Section 3.2): predicted experts among the activated ones, per layer
+      uint64_t hits = 0;
+      for (int l = 0; l < L; ++l)
+        for (int i = 0; i < k; ++i) {
+          bool found = false;
+          for (int j = 0; j < k; ++j) found |= pred[(size_t)l * k + j] == used[(size_t)l * k + i];
+          hits += found;
+        }
+      if (main_stack->sched && st.hint_hits != hits)
+        return fail(ODMOE_ESTATE, "the scheduler confirmed %llu hints, the index lists say %llu",
+                    (unsigned long long)st.hint_hits, (unsigned long long)hits);
+      recall_out[it] = (float)hits / (float)(L * k);
+      std::swap(xm, ym);   // main's output is its next input
+      std::swap(xs, ys);   // and the shadow's own output is what it follows when not aligned
+    }
+    if (x_final_dev) {
+      HIP_TRY(hipMemcpyAsync(x_final_dev, xm, row, hipMemcpyDeviceToDevice, main_stack->compute));
+      HIP_TRY(hipStreamSynchronize(main_stack->compute));
+    }
+    return ODMOE_OK;
+  };
+  rc = body();
+  (void)hipStreamSynchronize(main_stack->compute);
+  (void)hipStreamSynchronize(shadow->compute);
+  (void)hipFree(buf);
+  if (shadow_ms) *shadow_ms = (float)t_shadow;
+  if (main_ms) *main_ms = (float)t_main;
+  return rc;
+}
+
+int odmoe_sep_emulate(odmoe_layer_t* main_stack, odmoe_layer_t* shadow, const void* x0_dev, int32_t n_iter,
+                      int32_t aligned, float* recall_out, void* x_final_dev, float* shadow_ms, float* main_ms) {
+  return guarded([&] {
+    return sep_emulate_impl(main_stack, shadow, x0_dev, n_iter, aligned, recall_out, x_final_dev, shadow_ms, main_ms);
+  });
 }
 
 }  // extern "C"

@@ -53,7 +53,8 @@ class MoEStack:
     def __init__(self, cfg: synth.MoEConfig, layers: Optional[Sequence[LayerWeights]] = None,
                  unique_layers: Optional[int] = None, device: str = "cuda:0",
                  copy_stream: Optional[torch.cuda.Stream] = None, experts_in_host_memory: bool = False,
-                 buffers_of: Optional["MoEStack"] = None, buffer_layers: Optional[Sequence[int]] = None):
+                 buffers_of: Optional["MoEStack"] = None, buffer_layers: Optional[Sequence[int]] = None,
+                 device_buffers=None, expert_quant: int = B.ODMOE_Q_NONE):
         """layers: per-layer stored weights; generated from `cfg` when None.
 
         experts_in_host_memory (with cfg.n_slots == 0): the experts stay in pinned host memory and
@@ -65,13 +66,21 @@ class MoEStack:
         buffers_of: another stack of the same layers whose router and expert buffers this one
         shares instead of making its own copies (it must outlive this stack's use);
         buffer_layers picks which of its unique layers, in order (default: all of them).
+
+        device_buffers = (router tensors [U], bias tensors or None [U], expert tensors [U][E]):
+        buffers that already exist (device memory, or pinned host memory for a slot pool), for
+        example the quantised weights the library's quantiser wrote; `layers` is then not used.
+        expert_quant: the odmoe_quant format of the expert buffers (int8 rows for a shadow stack).
         """
         self.cfg = cfg
         self.device = device
         L, E = cfg.n_layers, cfg.n_experts
         U = L if unique_layers is None else min(unique_layers, L)
         self.unique_layers = U
-        if layers is None:
+        self.expert_quant = expert_quant
+        if device_buffers is not None:
+            layers = [None] * len(device_buffers[0])
+        elif layers is None:
             layers = [synth.layer_weights(cfg, l) for l in range(U)]
         assert len(layers) in (U, L)
         self.layers_np = list(layers)
@@ -85,7 +94,9 @@ class MoEStack:
                 uniq_router, uniq_bias, uniq_experts = ([lst[i] for i in buffer_layers]
                                                         for lst in (uniq_router, uniq_bias, uniq_experts))
             assert len(uniq_experts) == nl
-        for (Wg, b, experts) in ([] if buffers_of is not None else self.layers_np):
+        if device_buffers is not None:
+            uniq_router, uniq_bias, uniq_experts = (list(v) for v in device_buffers)
+        for (Wg, b, experts) in ([] if (buffers_of is not None or device_buffers is not None) else self.layers_np):
             uniq_router.append(to_device(Wg, device))
             uniq_bias.append(None if b is None else to_device(np.asarray(b, np.float32), device))
             if cfg.n_slots == 0 and not experts_in_host_memory:
@@ -99,7 +110,8 @@ class MoEStack:
             expert_w.extend(uniq_experts[u])
         self._keep = [uniq_router, uniq_bias, uniq_experts]
         c = B.odmoe_config(cfg.hidden, cfg.ffn, E, cfg.top_k, L, cfg.n_slots,
-                           B.ODMOE_F32 if cfg.dtype == "f32" else B.ODMOE_BF16, cfg.glue)
+                           B.ODMOE_F32 if cfg.dtype == "f32" else B.ODMOE_BF16, cfg.glue, expert_quant)
+        self.expert_bytes = B.odmoe_expert_bytes(c)
         self.stream = torch.cuda.current_stream(torch.device(device))
         self.copy_stream = copy_stream
         has_bias = any(b is not None for b in router_b)

@@ -1,96 +1,80 @@
-"""Shadow copies of a synthetic MoE stack and the emulation of OD-MoE's SEP predictor with them.
+"""Shadow copies of a synthetic MoE stack for the emulation of OD-MoE's SEP predictor.
 
 The paper's predictor (Sections 1, 3.2) runs a quantised copy of the model ahead of the
-full-precision one and uses its routing as the expert prediction; token / KV-cache alignment
-periodically resets the copy's state to the full model's.  Here the copy is a second stack on
-the same GPU whose weights went through a quantise -> dequantise round trip on the host (the
-kernels still run in the storage dtype: what is emulated is the routing drift that quantisation
-causes, not the copy's speed).  Its per-layer expert indices are handed to the full stack as
-`predicted_idx_host`; the full stack's router verifies them (hits / reloads = recall).
+full-precision one and uses its routing as the expert prediction.  Here the copy is a second
+stack on the same GPU, built from the full stack's stored weights by the library's own quantiser
+(`odmoe_quantize`, `odmoe_quantize_expert`):
 
-There is no attention and no KV cache in this build, so a "decode iteration" is emulated by
-feeding the stack's output back as the next token's input; "alignment" means the copy starts
-every iteration from the full stack's input instead of its own.
+  'bf16'  an identical copy (the predictor that is always right)
+  'int8'  experts as int8 codes with a scale per weight row, read by the int8 GEMV kernels (half
+          the bytes per token); the router quantised the same way and held dequantised in the
+          storage dtype (it is tiny)
+  'int4'  4 bits per weight in groups of 64, held dequantised in the storage dtype (there is no
+          4-bit GEMV: this copy shows the routing drift only, not the cost)
+
+This module only moves buffers and calls the library (marshalling); `emulate` is
+`odmoe_sep_emulate`.
 """
 from __future__ import annotations
 
 from typing import List, Sequence
 
-import numpy as np
+import torch
 
-from . import synth
-
-
-def _to_f32(stored: np.ndarray) -> np.ndarray:
-    return synth.bf16_bits_to_f32(stored) if stored.dtype == np.uint16 else stored.astype(np.float32)
+from . import binding as B
+from . import harness, synth
 
 
-def quantize_dequantize(W_f32: np.ndarray, kind: str, group: int = 64) -> np.ndarray:
-    """Round trip of a [rows, cols] matrix through symmetric absmax quantisation.
-    kind: 'bf16' (no change), 'int8' (per row, 127 levels each side), 'int4' (per group of
-    `group` elements of a row, 7 levels each side).  Rounding is half-to-even."""
-    W = W_f32.astype(np.float64)
-    if kind == "bf16":
-        return W
-    if kind == "int8":
-        s = np.abs(W).max(axis=1, keepdims=True) / 127.0
-        lim = 127
-    elif kind == "int4":
-        r, c = W.shape
-        if c % group:
-            raise ValueError("row length must be a multiple of the group size")
-        W = W.reshape(r, c // group, group)
-        s = np.abs(W).max(axis=2, keepdims=True) / 7.0
-        lim = 7
-    else:
+def _dtype_code(cfg: synth.MoEConfig) -> int:
+    return B.ODMOE_F32 if cfg.dtype == "f32" else B.ODMOE_BF16
+
+
+def shadow_stack(cfg: synth.MoEConfig, layers: Sequence, kind: str, device: str = "cuda:0") -> harness.MoEStack:
+    """A resident stack of cfg's shape whose weights are the `kind` copy of `layers` (stored
+    per-layer (Wg, b, experts) as synth makes them)."""
+    if kind not in ("bf16", "int8", "int4"):
         raise ValueError(kind)
-    div = np.where(s > 0, s, 1.0)
-    q = np.clip(np.rint(W / div), -lim, lim) * (s > 0)
-    out = q * s
-    return out.reshape(W_f32.shape)
-
-
-def shadow_layers(cfg: synth.MoEConfig, layers: Sequence, kind: str) -> List:
-    """Per-layer (Wg, b, experts) of the shadow copy, in cfg's storage dtype."""
-    out = []
-    H, F = cfg.hidden, cfg.ffn
+    rcfg = cfg.small(n_slots=0)
+    if kind == "bf16":
+        return harness.MoEStack(rcfg, list(layers), device=device)
+    dt, td = _dtype_code(cfg), harness.torch_dtype(cfg.dtype)
+    qkind = B.ODMOE_Q_INT8_ROW if kind == "int8" else B.ODMOE_Q_INT4_G64
+    H, F, E = cfg.hidden, cfg.ffn, cfg.n_experts
+    stream = torch.cuda.current_stream(torch.device(device)).cuda_stream
+    c = B.odmoe_config(H, F, E, cfg.top_k, 1, 0, dt, 0, B.ODMOE_Q_INT8_ROW)
+    q_bytes = B.odmoe_expert_bytes(c)
+    routers, biases, experts_all = [], [], []
     for (Wg, b, experts) in layers:
-        Wg_s = synth.store(quantize_dequantize(_to_f32(Wg), kind).astype(np.float32), cfg.dtype)
-        ex_s = []
+        src = harness.to_device(Wg, device)
+        r = torch.empty((E, H), dtype=td, device=device)
+        B.odmoe_quantize(src, dt, E, H, qkind, None, None, r, stream)
+        routers.append(r)
+        biases.append(None if b is None else harness.to_device(b, device))
+        ex: List[torch.Tensor] = []
         for flat in experts:
-            f = _to_f32(flat)
-            parts = [quantize_dequantize(f[:H * F].reshape(F, H), kind),
-                     quantize_dequantize(f[H * F:2 * H * F].reshape(F, H), kind),
-                     quantize_dequantize(f[2 * H * F:].reshape(H, F), kind)]
-            ex_s.append(synth.store(np.concatenate([p.ravel() for p in parts]).astype(np.float32), cfg.dtype))
-        out.append((Wg_s, b, ex_s))
-    return out
+            src = harness.to_device(flat, device)
+            if kind == "int8":
+                dst = torch.empty(q_bytes, dtype=torch.uint8, device=device)
+                B.odmoe_quantize_expert(c, src, dst, stream)
+            else:
+                dst = torch.empty(3 * H * F, dtype=td, device=device)
+                es = dst.element_size()
+                for part, (rows, cols) in enumerate(((F, H), (F, H), (H, F))):
+                    off = part * H * F * es
+                    B.odmoe_quantize(src.data_ptr() + off, dt, rows, cols, qkind, None, None, dst.data_ptr() + off, stream)
+            torch.cuda.synchronize()        # src may be freed
+            ex.append(dst)
+        experts_all.append(ex)
+    return harness.MoEStack(rcfg, device=device, device_buffers=(routers, biases, experts_all),
+                            unique_layers=len(routers),
+                            expert_quant=B.ODMOE_Q_INT8_ROW if kind == "int8" else B.ODMOE_Q_NONE)
 
 
-def emulate(main, shadow, x0, n_iter: int, aligned: bool, period: int = 1):
-    """Runs `n_iter` emulated decode iterations.
-
-    main, shadow: harness.MoEStack of the same shape (main may be cacheless).  x0: device tensor [H].
-    Each iteration the shadow stack produces its routing for all layers, the main stack decodes
-    with those as hints, and the main stack's output becomes the next input.  aligned=True
-    restarts the shadow from the main stack's input every `period` iterations (the alignment
-    period of Section 3.2; 1 = every iteration) and lets it follow its own outputs in between;
-    aligned=False never realigns.  Returns (recall per iteration: list of float, final main
-    output tensor).
-    """
-    if period < 1:
-        raise ValueError("period must be >= 1")
-    L, k = main.cfg.n_layers, main.cfg.top_k
-    x_main = x0
-    x_shadow = x0
-    recalls = []
-    for it in range(n_iter):
-        y_s, idx_s, _ = shadow.decode(x_main if (aligned and it % period == 0) else x_shadow)
-        y_m, idx_m, st = main.decode(x_main, pred=idx_s)
-        if main.cfg.n_slots > 0:
-            hits = st.hint_hits
-        else:  # resident main stack: count on the host
-            hits = sum(len(set(idx_s[l]) & set(idx_m[l])) for l in range(L))
-        recalls.append(hits / float(L * k))
-        x_main, x_shadow = y_m, y_s
-    return recalls, x_main
+def emulate(main: harness.MoEStack, shadow: harness.MoEStack, x0: torch.Tensor, n_iter: int, aligned: bool):
+    """`n_iter` emulated decode iterations (odmoe_sep_emulate): the shadow stack's routing is the
+    main stack's prediction, main's output is its next input; aligned=True restarts the shadow from
+    main's input every iteration.  Returns (recall per iteration, main's final output tensor,
+    wall ms spent in the shadow's steps, wall ms spent in main's steps)."""
+    x_end = torch.empty_like(x0)
+    rec, shadow_ms, main_ms = B.odmoe_sep_emulate(main.handle, shadow.handle, x0, n_iter, aligned, x_end)
+    return rec, x_end, shadow_ms, main_ms

@@ -35,7 +35,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_header():
     from paper_2512_03927_amd import binding as B
-    assert ctypes.sizeof(B.odmoe_config) == 32
+    assert ctypes.sizeof(B.odmoe_config) == 36
     assert ctypes.sizeof(B.odmoe_stats) == 56
     assert B.odmoe_stats.h2d_bytes.offset == 24
 
@@ -45,12 +45,14 @@ def test_argument_errors_need_no_gpu():
     from paper_2512_03927_amd import binding as B
     lib = B.lib()
     out = ctypes.c_void_p()
-    bad = B.odmoe_config(hidden=100, ffn=64, n_experts=4, top_k=2, n_layers=1, n_slots=0, dtype=0, glue=0)
+    bad = B.odmoe_config(hidden=100, ffn=64, n_experts=4, top_k=2, n_layers=1, n_slots=0, dtype=0, glue=0,
+                         expert_quant=0)
     assert lib.odmoe_layer_init(ctypes.byref(bad), None, None, None, None, None, ctypes.byref(out)) == B.ODMOE_EINVAL
     assert "multiples of 8" in B.odmoe_last_error()
     for kw in (dict(top_k=9), dict(top_k=5), dict(n_slots=1), dict(dtype=7), dict(n_experts=0), dict(n_layers=0),
-               dict(glue=2), dict(ffn=1 << 20)):
-        base = dict(hidden=64, ffn=64, n_experts=4, top_k=2, n_layers=1, n_slots=0, dtype=0, glue=0)
+               dict(glue=2), dict(ffn=1 << 20), dict(expert_quant=2), dict(expert_quant=1, hidden=72),
+               dict(expert_quant=1, hidden=16384)):
+        base = dict(hidden=64, ffn=64, n_experts=4, top_k=2, n_layers=1, n_slots=0, dtype=0, glue=0, expert_quant=0)
         base.update(kw)
         c = B.odmoe_config(**base)
         assert lib.odmoe_layer_init(ctypes.byref(c), None, None, None, None, None, ctypes.byref(out)) == B.ODMOE_EINVAL
@@ -58,6 +60,15 @@ def test_argument_errors_need_no_gpu():
     assert lib.odmoe_route_topk(None, 0, None, 1, None, None) == B.ODMOE_EINVAL
     assert lib.odmoe_decode_step(None, None, None, None, None, None) == B.ODMOE_EINVAL
     assert lib.odmoe_layer_destroy(None) == B.ODMOE_OK
+    # expert buffer sizes: stored dtype, and int8 codes plus one fp32 scale per weight row
+    c = B.odmoe_config(4096, 14336, 8, 2, 1, 0, B.ODMOE_BF16, 0, B.ODMOE_Q_NONE)
+    assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 * 2 == 352321536
+    c.expert_quant = B.ODMOE_Q_INT8_ROW
+    assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 + 4 * (2 * 14336 + 4096)
+    assert B.odmoe_expert_bytes(bad) == 0
+    assert lib.odmoe_quantize(None, 1, 4, 64, 1, None, None, None, None) == B.ODMOE_EINVAL
+    assert lib.odmoe_quantize(1, 1, 4, 100, 2, None, None, None, None) == B.ODMOE_EINVAL     # 4-bit groups of 64
+    assert lib.odmoe_quantize(1, 1, 4, 64, 7, None, None, None, None) == B.ODMOE_EINVAL
 
 
 def test_load_window_matches_oracle_and_worked_example():

@@ -1,16 +1,25 @@
-"""Emulated SEP predictor on the GPU: a quantised shadow stack supplies the expert hints.
+"""The shadow model's side on the GPU (paper Sections 1, 3.2): the device quantiser, the int8
+expert GEMVs, and the emulated SEP predictor built from them.
 
-What must hold whatever the weights: hints never change the full stack's output; an identical
-copy predicts perfectly; the confirmed fraction equals the recall of Section 3.2 computed by the
-oracle from the two index lists; a coarser copy is not better; without alignment recall decays.
+Bars: quantiser codes, scales and dequantised weights bit-exact against oracle/sep_oracle.py
+(integer decisions, taken in float64 on both sides); the int8 layer within the bf16 / fp32
+tolerances of the layer definition evaluated by the oracle on the dequantised weights
+code * float32(scale); routing of the int8 stack bit-exact against the oracle on those weights.
+What must hold for the emulation whatever the weights: hints never change the full stack's
+output; an identical copy predicts perfectly; the reported recall is the recall of Section 3.2
+computed by the oracle from the two index lists; a coarser copy is not better; without alignment
+recall decays.
 """
 import numpy as np
 import pytest
 
 from oracle import moe_oracle as O
-from paper_2512_03927_amd import shadow, synth
+from oracle import sep_oracle as S
+from paper_2512_03927_amd import synth
 
 pytestmark = pytest.mark.gpu
+BF16_REL = 2e-2
+ONE_BF16_ROUNDING = 1.5 * 2.0 ** -8
 
 
 @pytest.fixture(scope="module")
@@ -19,13 +28,152 @@ def H():
     return harness
 
 
+def _quantize_on_device(H, W_stored, dtype, kind):
+    import torch
+    from paper_2512_03927_amd import binding as B
+    rows, cols = W_stored.shape
+    w = H.to_device(W_stored)
+    code = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda:0")
+    n_scale = rows if kind == B.ODMOE_Q_INT8_ROW else rows * (cols // 64)
+    scale = torch.zeros(n_scale, dtype=torch.float32, device="cuda:0")
+    deq = torch.zeros_like(w)
+    B.odmoe_quantize(w, B.ODMOE_F32 if dtype == "f32" else B.ODMOE_BF16, rows, cols, kind, code, scale, deq,
+                     torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return code.cpu().numpy(), scale.cpu().numpy(), H.from_device(deq)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("rows,cols", [(7, 96), (48, 128), (3, 4096), (130, 64), (1, 8), (5, 14336)])
+def test_device_quantiser_int8_rows_is_bit_exact(H, dtype, rows, cols):
+    from paper_2512_03927_amd import binding as B
+    W = synth.store(synth.normal(1, 3 + rows, rows * cols, 0.02).reshape(rows, cols), dtype)
+    if rows > 2:
+        W[2] = 0                                               # an all-zero row: scale 0, codes 0
+    code, scale, deq = _quantize_on_device(H, W, dtype, B.ODMOE_Q_INT8_ROW)
+    q, s = S.quantize_rows_int8(O.widen(W))
+    assert np.array_equal(code.astype(np.int32) - 128, q.astype(np.int32))
+    assert np.array_equal(scale, s.astype(np.float32))
+    assert np.array_equal(deq, O.round_to_storage(S.dequantize_rows(q, s), dtype))
+
+
+def test_device_quantiser_half_to_even_and_clipping(H):
+    """Rows whose scale is exactly 1 (largest element 127): values on .5 go to the even code."""
+    from paper_2512_03927_amd import binding as B
+    W = np.zeros((2, 16), np.float32)
+    W[0, :8] = [127.0, 0.5, 1.5, 2.5, -0.5, -1.5, 63.49, -126.51]
+    W[1, :5] = [-127.0, 126.5, -125.5, 3.5, 4.5]
+    code, scale, deq = _quantize_on_device(H, W, "f32", B.ODMOE_Q_INT8_ROW)
+    assert scale.tolist() == [1.0, 1.0]
+    assert (code[0, :8].astype(int) - 128).tolist() == [127, 0, 2, 2, 0, -2, 63, -127]
+    assert (code[1, :5].astype(int) - 128).tolist() == [-127, 126, -126, 4, 4]
+    q, s = S.quantize_rows_int8(W.astype(np.float64))
+    assert np.array_equal(code.astype(np.int32) - 128, q.astype(np.int32))
+    assert np.array_equal(deq, S.dequantize_rows(q, s).astype(np.float32))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_device_quantiser_int4_groups_is_bit_exact(H, dtype):
+    from paper_2512_03927_amd import binding as B
+    rows, cols = 9, 320
+    W = synth.store(synth.normal(2, 5, rows * cols, 1.0).reshape(rows, cols), dtype)
+    W[4, 64:128] = 0
+    code, scale, deq = _quantize_on_device(H, W, dtype, B.ODMOE_Q_INT4_G64)
+    q, s = S.quantize_groups_int4(O.widen(W), 64)
+    assert np.array_equal(code.astype(np.int32) - 8, q.astype(np.int32))
+    assert np.array_equal(scale.reshape(rows, cols // 64), s.astype(np.float32))
+    assert np.array_equal(deq, O.round_to_storage(S.dequantize_groups(q, s, 64), dtype))
+
+
+def _oracle_int8_layer(cfg, layer):
+    """(Wg', b, experts') the int8 shadow copy holds, as float64: router = stored(q * s) as the
+    device writes it, experts = q * float32(s) as the int8 GEMVs read them."""
+    Wg, b, experts = layer
+    Hd, F = cfg.hidden, cfg.ffn
+    Wg_s = O.round_to_storage(S.shadow_matrix(O.widen(Wg), "int8"), cfg.dtype)
+    ex = []
+    for flat in experts:
+        parts = []
+        for W in O.split_expert(flat, Hd, F):
+            q, s = S.quantize_rows_int8(O.widen(W))
+            parts.append(S.dequantize_rows(q, s.astype(np.float32)))
+        ex.append(tuple(parts))
+    return Wg_s, b, ex
+
+
+Q8_SHAPES = [
+    # H, F, E, k, dtype
+    (528, 1040, 8, 2, "bf16"),       # ragged tails: one chunk of 1024 codes plus a piece
+    (2048, 1408, 8, 6, "bf16"),      # the fine-grained layer shape (config 5), k = 6
+    (1024, 2816, 16, 4, "bf16"),
+    (16, 16, 2, 1, "bf16"),          # the smallest shape int8 experts take
+    (272, 528, 5, 3, "f32"),         # fp32 activations over int8 experts
+    (6144, 64, 4, 2, "bf16"),        # six register chunks in the w1/w3 GEMV
+    (64, 40960, 3, 2, "bf16"),       # the longest ffn vector: 40 chunks over ten waves
+    (4096, 14336, 4, 2, "bf16"),     # the Mixtral layer shape
+]
+
+
+@pytest.mark.parametrize("Hd,F,E,k,dtype", Q8_SHAPES)
+def test_int8_expert_layer_matches_oracle_on_dequantised_weights(H, Hd, F, E, k, dtype):
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=3 if Hd * F < (1 << 24) else 2, seed=61)
+    layer = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Wg_s, b, ex_s = _oracle_int8_layer(cfg, layer)
+    with shadow.shadow_stack(cfg, [layer], "int8") as st:
+        assert st.expert_bytes == 3 * Hd * F + 4 * (2 * F + Hd)
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        yn = H.from_device(st.ffn(0, idx, gate, x))              # int8 experts always run token by token
+        ids = idx.cpu().numpy()
+        for t in range(cfg.n_tokens):
+            y_ref, idx_ref, _ = O.moe_layer(X[t], Wg_s, b, ex_s, k)
+            assert np.array_equal(ids[t], idx_ref)
+            err = np.max(np.abs(O.widen(yn[t]) - y_ref))
+            if dtype == "f32":
+                assert err <= 1e-4
+            else:
+                assert err <= ONE_BF16_ROUNDING * np.max(np.abs(y_ref)), (t, err / np.max(np.abs(y_ref)))
+            yt, idx_t, _ = st.decode(x[t])                       # the fused per-token entry point
+            assert np.array_equal(H.from_device(yt), yn[t]) and np.array_equal(idx_t[0], idx_ref)
+
+
+def test_int8_stack_cacheless_and_resident_agree_and_move_half_the_bytes(H):
+    """int8 experts through the slot pool: the same bits as resident, and each load is the int8
+    expert's size (half of bf16 plus the scales)."""
+    import torch
+    from paper_2512_03927_amd import binding as B
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=5, n_slots=4, dtype="bf16", n_tokens=2, glue=1, seed=63)
+    layers = [synth.layer_weights(cfg, l) for l in range(cfg.n_layers)]
+    X = synth.tokens(cfg)
+    with shadow.shadow_stack(cfg, layers, "int8") as res:
+        routers, biases, experts = res._keep
+        pinned = [[torch.empty(e.shape, dtype=e.dtype, pin_memory=True).copy_(e) for e in ex] for ex in experts]
+        with H.MoEStack(cfg, device_buffers=(routers, biases, pinned), unique_layers=cfg.n_layers,
+                        expert_quant=B.ODMOE_Q_INT8_ROW) as st:
+            assert st.expert_bytes < cfg.expert_bytes * 0.51
+            layers_o = [_oracle_int8_layer(cfg, l) for l in layers]
+            for t in range(cfg.n_tokens):
+                x = H.to_device(X[t])
+                y_r, idx_r, _ = res.decode(x)
+                y_c, idx_c, s = st.decode(x)
+                assert np.array_equal(idx_c, idx_r) and np.array_equal(H.from_device(y_c), H.from_device(y_r))
+                assert s.loads == cfg.n_layers * cfg.top_k and s.h2d_bytes == s.loads * st.expert_bytes
+                x_ref, IDX, _ = O.stack_decode(X[t], layers_o, cfg.top_k, "bf16", glue=1)
+                assert np.array_equal(idx_c, IDX)
+                ref = O.widen(x_ref)
+                assert np.max(np.abs(O.widen(H.from_device(y_c)) - ref)) <= BF16_REL * np.max(np.abs(ref))
+
+
 def test_shadow_stack_hints(H):
+    from paper_2512_03927_amd import shadow
     cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=8, n_slots=4, dtype="bf16", n_tokens=1, glue=1, seed=41)
     layers = [synth.layer_weights(cfg, l) for l in range(cfg.n_layers)]
     x0 = H.to_device(synth.tokens(cfg)[0])
     n_iter = 24
     L, k = cfg.n_layers, cfg.top_k
-    res_cfg = cfg.small(n_slots=0)
     with H.MoEStack(cfg, layers) as main:
         # reference chain without any hints
         x, base = x0, []
@@ -34,27 +182,24 @@ def test_shadow_stack_hints(H):
             base.append((H.from_device(x).copy(), idx.copy()))
         rec = {}
         for kind in ("bf16", "int8", "int4"):
-            with H.MoEStack(res_cfg, shadow.shadow_layers(cfg, layers, kind)) as sh:
+            with shadow.shadow_stack(cfg, layers, kind) as sh:
                 for aligned in (True, False):
-                    r, x_end = shadow.emulate(main, sh, x0, n_iter, aligned)
+                    r, x_end, shadow_ms, main_ms = shadow.emulate(main, sh, x0, n_iter, aligned)
                     rec[(kind, aligned)] = r
+                    assert shadow_ms > 0 and main_ms > 0
                     # hints change timing only: the main chain ends in the same bits
                     assert np.array_equal(H.from_device(x_end), base[-1][0])
-                if kind == "int4":
-                    # alignment period: period 1 is the aligned run, a period longer than the run
-                    # is the free-running one, and iterations right after a realignment equal the
-                    # aligned run's (same input, same weights)
-                    assert shadow.emulate(main, sh, x0, n_iter, True, 1)[0] == rec[(kind, True)]
-                    assert shadow.emulate(main, sh, x0, n_iter, True, n_iter + 1)[0] == rec[(kind, False)]
-                    r4 = shadow.emulate(main, sh, x0, n_iter, True, 4)[0]
-                    assert r4[0::4] == rec[(kind, True)][0::4]
-                    rec[(kind, 4)] = r4
-                # recall bookkeeping against the oracle's definition, first iteration, aligned
+                # the reported recall is the definition's (Section 3.2), first iteration, aligned
                 _, idx_s, _ = sh.decode(x0)
                 _, idx_m, st = main.decode(x0, pred=idx_s)
                 c = np.array([[[O.correct_predictions(idx_s[l], idx_m[l]) for l in range(L)]]])
+                assert abs(O.recall(c, np.ones((1, 1)), k) - rec[(kind, True)][0]) < 1e-6
                 assert abs(O.recall(c, np.ones((1, 1)), k) - st.hint_hits / (L * k)) < 1e-12
                 assert st.reloads == L * k - st.hint_hits
+        # the same emulation with a resident main stack counts the recall from the index lists
+        with H.MoEStack(cfg.small(n_slots=0), layers) as main_res, shadow.shadow_stack(cfg, layers, "int8") as sh:
+            r, x_end, _, _ = shadow.emulate(main_res, sh, x0, n_iter, True)
+            assert r == rec[("int8", True)] and np.array_equal(H.from_device(x_end), base[-1][0])
     assert all(v == 1.0 for v in rec[("bf16", True)]) and all(v == 1.0 for v in rec[("bf16", False)])
     m = {key: float(np.mean(v)) for key, v in rec.items()}
     print("mean recall:", {f"{k_}-{a}": round(v, 3) for (k_, a), v in m.items()})

@@ -1,10 +1,11 @@
-"""Quantisers of the shadow-model emulation: oracle pins, and product == oracle bit for bit (CPU)."""
+"""Quantisers of the shadow-model emulation: pins of oracle/sep_oracle.py (CPU).  The product's
+quantiser runs on the GPU and is compared with this oracle bit for bit in tests/test_gpu_sep.py."""
 import numpy as np
 import pytest
 
 from oracle import moe_oracle as O
 from oracle import sep_oracle as S
-from paper_2512_03927_amd import shadow, synth
+from paper_2512_03927_amd import synth
 
 rng = np.random.default_rng(5)
 
@@ -49,28 +50,30 @@ def test_int4_groups():
     assert s[0, 0] == 1.0 and q[0, :5].tolist() == [7, -4, 2, 0, -7]
 
 
-@pytest.mark.parametrize("kind", ["bf16", "int8", "int4"])
-def test_product_quantiser_equals_oracle_bit_for_bit(kind):
-    W = synth.normal(1, 3, 48 * 128, 0.02).reshape(48, 128)
+def test_shadow_matrix_kinds():
+    W = synth.normal(1, 3, 48 * 128, 0.02).reshape(48, 128).astype(np.float64)
     W[5] = 0
-    got = shadow.quantize_dequantize(W, kind)
-    want = S.shadow_matrix(W.astype(np.float64), kind)
-    assert np.array_equal(got, want)
+    assert np.array_equal(S.shadow_matrix(W, "bf16"), W)
+    q, sc = S.quantize_rows_int8(W)
+    assert np.array_equal(S.shadow_matrix(W, "int8"), q.astype(np.float64) * sc[:, None])
+    q4, s4 = S.quantize_groups_int4(W)
+    assert np.array_equal(S.shadow_matrix(W, "int4"), S.dequantize_groups(q4, s4))
+    step = np.abs(W).max(axis=1, keepdims=True) / 127
+    assert (np.abs(W - S.shadow_matrix(W, "int8")) <= step / 2 + 1e-18).all()
+    with pytest.raises(ValueError):
+        S.shadow_matrix(W, "int3")
 
 
-def test_shadow_layers_keep_layout_and_bf16_copy_is_identical():
-    cfg = synth.MoEConfig("t", 64, 128, 4, 2, n_layers=2, dtype="bf16")
-    layers = [synth.layer_weights(cfg, l) for l in range(2)]
-    same = shadow.shadow_layers(cfg, layers, "bf16")
-    for (a, _, ea), (b, _, eb) in zip(layers, same):
-        assert np.array_equal(a, b) and all(np.array_equal(x, y) for x, y in zip(ea, eb))
-    q8 = shadow.shadow_layers(cfg, layers, "int8")
-    assert q8[0][2][1].shape == layers[0][2][1].shape and q8[0][2][1].dtype == np.uint16
-    # the int8 copy differs, but by less than half a quantisation step plus one bf16 rounding
-    W1 = O.widen(layers[0][2][1])[:64 * 128].reshape(128, 64)
-    W1s = O.widen(q8[0][2][1])[:64 * 128].reshape(128, 64)
-    step = np.abs(W1).max(axis=1, keepdims=True) / 127
-    assert (np.abs(W1 - W1s) <= step / 2 + np.abs(W1) * 2.0 ** -8).all() and not np.array_equal(W1, W1s)
+def _oracle_shadow_layers(cfg, layers, kind):
+    """Shadow copy of a stack through the oracle's quantisers, stored back in cfg's dtype."""
+    out = []
+    for (Wg, b, experts) in layers:
+        ex = []
+        for flat in experts:
+            parts = [S.shadow_matrix(O.widen(W), kind) for W in O.split_expert(flat, cfg.hidden, cfg.ffn)]
+            ex.append(O.round_to_storage(np.concatenate([p.ravel() for p in parts]), cfg.dtype))
+        out.append((O.round_to_storage(S.shadow_matrix(O.widen(Wg), kind), cfg.dtype), b, ex))
+    return out
 
 
 def test_oracle_shadow_routing_recall_decreases_with_coarser_quantisation():
@@ -81,7 +84,7 @@ def test_oracle_shadow_routing_recall_decreases_with_coarser_quantisation():
     X = synth.tokens(cfg)
     rec = {}
     for kind in ("bf16", "int8", "int4"):
-        sh_layers = shadow.shadow_layers(cfg, layers, kind)
+        sh_layers = _oracle_shadow_layers(cfg, layers, kind)
         c = np.zeros((1, cfg.n_tokens, cfg.n_layers))
         for t in range(cfg.n_tokens):
             _, idx_m, _ = O.stack_decode(X[t], layers, cfg.top_k, "f32")
