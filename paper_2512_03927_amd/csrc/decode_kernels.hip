@@ -98,6 +98,37 @@ __device__ __forceinline__ void stage_vec(const T* __restrict__ src, float* __re
 }
 
 // ---------------------------------------------------------------------------------------------
+// Inter-layer glue for one block: z = x + y, out = z / sqrt(mean(z^2) + 1e-6), rounded to the
+// storage dtype and handed element by element to `store`.  The sum of squares is taken in the
+// order of a block of 1024 threads (thread v sums elements v, v + 1024, ...; waves of 64
+// consecutive threads are reduced as a tree; the 16 wave sums are added in order), whatever the
+// real block size (any divisor of 1024 that is a multiple of 64): the stand-alone glue kernel and
+// the router kernels that start with the glue give the same bits.  part: 16 floats of LDS.
+// ---------------------------------------------------------------------------------------------
+template <typename T, typename Store>
+__device__ __forceinline__ void glue_block(const T* __restrict__ xp, const T* __restrict__ yp, int H,
+                                           float* part, Store store) {
+  const int lane = threadIdx.x & 63;
+  for (int v = threadIdx.x; v < 1024; v += blockDim.x) {
+    float ss = 0.f;
+    for (int i = v; i < H; i += 1024) {
+      const float z = DT<T>::to_f32(xp[i]) + DT<T>::to_f32(yp[i]);
+      ss = fmaf(z, z, ss);
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) part[v >> 6] = ss;
+  }
+  __syncthreads();
+  float tot = 0.f;
+  for (int w = 0; w < 16; ++w) tot += part[w];
+  const float scale = 1.f / sqrtf(tot / (float)H + 1e-6f);
+  for (int i = threadIdx.x; i < H; i += blockDim.x) {
+    const float z = DT<T>::to_f32(xp[i]) + DT<T>::to_f32(yp[i]);
+    store(i, DT<T>::from_f32(z * scale));
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Router GEMV + top-k + renormalised softmax gate.
 // Logits are summed in float64 and rounded once to fp32, so the selection agrees with a float64
 // reference rounded the same way regardless of summation order.  Ties: lowest index first.
@@ -179,8 +210,18 @@ __device__ __forceinline__ void select_topk_and_gate(const float* slog, float* s
   }
 }
 
-// One block per token: one wave per expert, in rounds.
+// The glue of the previous layer done at the head of a router kernel (one token): the router's
+// input x = rmsnorm(x_prev + y_prev) is made in LDS by every block, and written to x_out by one.
 template <typename T>
+struct GlueIn {
+  const T* x_prev;
+  const T* y_prev;
+  T* x_out;
+};
+
+// One block per token: one wave per expert, in rounds.  GLUE: one token whose input comes out of
+// the previous layer's glue, computed here first (dynamic LDS: H elements of T).
+template <typename T, bool GLUE>
 __global__ __launch_bounds__(512) void route_topk_kernel(const T* __restrict__ Wg,
                                                           const float* __restrict__ bias,
                                                           const T* __restrict__ x, int H, int E, int k,
@@ -189,13 +230,21 @@ __global__ __launch_bounds__(512) void route_topk_kernel(const T* __restrict__ W
                                                           int32_t* __restrict__ idx_mirror,
                                                           const void* const* __restrict__ table,
                                                           int table_off,
-                                                          const void** __restrict__ eptr_out) {
+                                                          const void** __restrict__ eptr_out, GlueIn<T> gl) {
   __shared__ float slog[ODMOE_MAX_EXPERTS];
   __shared__ float sel_v[ODMOE_MAX_TOPK];
   __shared__ int sel_i[ODMOE_MAX_TOPK];
+  extern __shared__ __attribute__((aligned(16))) unsigned char glue_lds[];
   const int t = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const T* xt = x + (size_t)t * H;
+  if constexpr (GLUE) {
+    __shared__ float part[16];
+    T* sx = reinterpret_cast<T*>(glue_lds);
+    glue_block<T>(gl.x_prev, gl.y_prev, H, part, [&](int i, T v) { sx[i] = v; gl.x_out[i] = v; });
+    __syncthreads();
+    xt = sx;
+  }
   const int nvec = H / DT<T>::VEC;
   for (int e = wave; e < E; e += nw) {
     const double acc = wave_logit<T>(Wg + (size_t)e * H, xt, nvec, lane);
@@ -209,21 +258,31 @@ __global__ __launch_bounds__(512) void route_topk_kernel(const T* __restrict__ W
 // the router matrix is read by many CUs at once.  The logits go to `logits` [T, E]; the block
 // that finishes last for its token (a ticket from counters[t], which it leaves at zero again)
 // does the selection.  No block waits for another.
-template <typename T>
+template <typename T, bool GLUE>
 __global__ __launch_bounds__(512) void route_topk_split_kernel(
     const T* __restrict__ Wg, const float* __restrict__ bias, const T* __restrict__ x, int H, int E, int k,
     int32_t* __restrict__ idx, float* __restrict__ gate, int32_t* __restrict__ idx_mirror,
     const void* const* __restrict__ table, int table_off, const void** __restrict__ eptr_out,
-    float* logits, int32_t* counters) {
+    float* logits, int32_t* counters, GlueIn<T> gl) {
   __shared__ float slog[ODMOE_MAX_EXPERTS];
   __shared__ float sel_v[ODMOE_MAX_TOPK];
   __shared__ int sel_i[ODMOE_MAX_TOPK];
   __shared__ int s_ticket;
+  extern __shared__ __attribute__((aligned(16))) unsigned char glue_lds[];
   const int t = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int e = blockIdx.x * 8 + wave;
+  const T* xt = x + (size_t)t * H;
+  if constexpr (GLUE) {   // every block makes the router's input for itself; block 0 also publishes it
+    __shared__ float part[16];
+    T* sx = reinterpret_cast<T*>(glue_lds);
+    const bool publish = blockIdx.x == 0;
+    glue_block<T>(gl.x_prev, gl.y_prev, H, part, [&](int i, T v) { sx[i] = v; if (publish) gl.x_out[i] = v; });
+    __syncthreads();
+    xt = sx;
+  }
   if (e < E) {
-    const double acc = wave_logit<T>(Wg + (size_t)e * H, x + (size_t)t * H, H / DT<T>::VEC, lane);
+    const double acc = wave_logit<T>(Wg + (size_t)e * H, xt, H / DT<T>::VEC, lane);
     if (lane == 0)
       __hip_atomic_store(logits + (size_t)t * E + e, (float)(acc + (bias ? (double)bias[e] : 0.0)),
                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -318,22 +377,7 @@ __global__ __launch_bounds__(512) void ffn_down_kernel(ExpertSrc src, const int3
 template <typename T>
 __global__ __launch_bounds__(1024) void glue_kernel(const T* x, const T* y, T* out, int H) {
   __shared__ float part[16];
-  float ss = 0.f;
-  for (int i = threadIdx.x; i < H; i += blockDim.x) {
-    float z = DT<T>::to_f32(x[i]) + DT<T>::to_f32(y[i]);
-    ss = fmaf(z, z, ss);
-  }
-  ss = wave_sum(ss);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  if (lane == 0) part[wave] = ss;
-  __syncthreads();
-  float tot = 0.f;
-  for (int w = 0; w < nw; ++w) tot += part[w];
-  const float scale = 1.f / sqrtf(tot / (float)H + 1e-6f);
-  for (int i = threadIdx.x; i < H; i += blockDim.x) {
-    float z = DT<T>::to_f32(x[i]) + DT<T>::to_f32(y[i]);
-    out[i] = DT<T>::from_f32(z * scale);
-  }
+  glue_block<T>(x, y, H, part, [&](int i, T v) { out[i] = v; });
 }
 
 // =============================================================================================
@@ -606,37 +650,60 @@ hipError_t kernels_init() {
   return hipSuccess;
 }
 
-hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
-                             const void* x, int32_t T, int32_t* idx, float* gate,
-                             int32_t* idx_mirror, const void* const* table, int32_t table_off,
-                             const void** eptr_out, const RouteScratch* scratch) {
-  if (T <= 0) return hipSuccess;
+namespace {
+template <typename T, bool GLUE>
+hipError_t launch_route_t(hipStream_t s, const Shape& sh, const void* Wg, const float* b, const void* x,
+                          int32_t T_tokens, int32_t* idx, float* gate, int32_t* idx_mirror,
+                          const void* const* table, int32_t table_off, const void** eptr_out,
+                          const RouteScratch* scratch, GlueIn<T> gl) {
+  const size_t lds = GLUE ? (size_t)sh.H * sizeof(T) : 0;
   // (up to 16 experts, two rounds of one block cost less than the tickets of the spread variant:
   // 4.3-6.8 us against 6.7-8.1 us; at 32 experts one block takes 18-22 us, the spread variant 9-10)
   const int split_from = g_tune_route_split_e > 0 ? g_tune_route_split_e : 17;
-  if (scratch && scratch->logits && sh.E >= split_from && T <= scratch->max_tokens) {
-    const dim3 grid((sh.E + 7) / 8, T);
-    if (sh.dtype == ODMOE_F32)
-      route_topk_split_kernel<float><<<grid, 512, 0, s>>>(
-          static_cast<const float*>(Wg), b, static_cast<const float*>(x), sh.H, sh.E, sh.k, idx, gate,
-          idx_mirror, table, table_off, eptr_out, scratch->logits, scratch->counters);
-    else
-      route_topk_split_kernel<bf16_t><<<grid, 512, 0, s>>>(
-          static_cast<const bf16_t*>(Wg), b, static_cast<const bf16_t*>(x), sh.H, sh.E, sh.k, idx, gate,
-          idx_mirror, table, table_off, eptr_out, scratch->logits, scratch->counters);
+  if (scratch && scratch->logits && sh.E >= split_from && T_tokens <= scratch->max_tokens) {
+    const dim3 grid((sh.E + 7) / 8, T_tokens);
+    route_topk_split_kernel<T, GLUE><<<grid, 512, lds, s>>>(static_cast<const T*>(Wg), b, static_cast<const T*>(x),
+                                                            sh.H, sh.E, sh.k, idx, gate, idx_mirror, table,
+                                                            table_off, eptr_out, scratch->logits,
+                                                            scratch->counters, gl);
     return hipGetLastError();
   }
   // one wave per expert up to 8 waves
   const int threads = sh.E >= 8 ? 512 : (sh.E >= 4 ? 256 : 128);
-  if (sh.dtype == ODMOE_F32)
-    route_topk_kernel<float><<<T, threads, 0, s>>>(static_cast<const float*>(Wg), b,
-                                                   static_cast<const float*>(x), sh.H, sh.E, sh.k, idx,
-                                                   gate, idx_mirror, table, table_off, eptr_out);
-  else
-    route_topk_kernel<bf16_t><<<T, threads, 0, s>>>(static_cast<const bf16_t*>(Wg), b,
-                                                    static_cast<const bf16_t*>(x), sh.H, sh.E, sh.k,
-                                                    idx, gate, idx_mirror, table, table_off, eptr_out);
+  route_topk_kernel<T, GLUE><<<T_tokens, threads, lds, s>>>(static_cast<const T*>(Wg), b, static_cast<const T*>(x),
+                                                            sh.H, sh.E, sh.k, idx, gate, idx_mirror, table,
+                                                            table_off, eptr_out, gl);
   return hipGetLastError();
+}
+}  // namespace
+
+bool route_glue_fusable(const Shape& sh) {
+  return (size_t)sh.H * (sh.dtype == ODMOE_F32 ? 4 : 2) <= 32 * 1024;   // the router's input in LDS
+}
+
+hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
+                             const void* x, int32_t T, int32_t* idx, float* gate,
+                             int32_t* idx_mirror, const void* const* table, int32_t table_off,
+                             const void** eptr_out, const RouteScratch* scratch, const void* glue_x_prev,
+                             const void* glue_y_prev, void* glue_x_out) {
+  if (T <= 0) return hipSuccess;
+  if (glue_x_prev) {
+    if (T != 1 || !glue_y_prev || !glue_x_out || !route_glue_fusable(sh)) return hipErrorInvalidValue;
+    if (sh.dtype == ODMOE_F32)
+      return launch_route_t<float, true>(s, sh, Wg, b, nullptr, 1, idx, gate, idx_mirror, table, table_off, eptr_out,
+                                         scratch, GlueIn<float>{static_cast<const float*>(glue_x_prev),
+                                                                static_cast<const float*>(glue_y_prev),
+                                                                static_cast<float*>(glue_x_out)});
+    return launch_route_t<bf16_t, true>(s, sh, Wg, b, nullptr, 1, idx, gate, idx_mirror, table, table_off, eptr_out,
+                                        scratch, GlueIn<bf16_t>{static_cast<const bf16_t*>(glue_x_prev),
+                                                                static_cast<const bf16_t*>(glue_y_prev),
+                                                                static_cast<bf16_t*>(glue_x_out)});
+  }
+  if (sh.dtype == ODMOE_F32)
+    return launch_route_t<float, false>(s, sh, Wg, b, x, T, idx, gate, idx_mirror, table, table_off, eptr_out,
+                                        scratch, GlueIn<float>{nullptr, nullptr, nullptr});
+  return launch_route_t<bf16_t, false>(s, sh, Wg, b, x, T, idx, gate, idx_mirror, table, table_off, eptr_out,
+                                       scratch, GlueIn<bf16_t>{nullptr, nullptr, nullptr});
 }
 
 namespace {

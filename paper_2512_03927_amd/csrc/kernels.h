@@ -48,10 +48,16 @@ constexpr int32_t ROUTE_SPLIT_MAX_TOKENS = 16;
 // kernel also stores table[table_off + idx] there (T*k pointers), which saves the FFN kernels
 // one dependent load.  With a scratch, more than 16 experts and T <= scratch->max_tokens the
 // experts of a token are spread over several blocks (same results).
+// With glue_x_prev != null (T must be 1, route_glue_fusable(sh) true) the token's input is the
+// previous layer's glue, done at the head of the same kernel: x = rmsnorm(glue_x_prev +
+// glue_y_prev) is written to glue_x_out (the bits launch_glue gives) and routed; `x` is not read.
 hipError_t launch_route_topk(hipStream_t s, const Shape& sh, const void* Wg, const float* b,
                              const void* x, int32_t T, int32_t* idx, float* gate,
                              int32_t* idx_mirror, const void* const* table, int32_t table_off,
-                             const void** eptr_out, const RouteScratch* scratch = nullptr);
+                             const void** eptr_out, const RouteScratch* scratch = nullptr,
+                             const void* glue_x_prev = nullptr, const void* glue_y_prev = nullptr,
+                             void* glue_x_out = nullptr);
+bool route_glue_fusable(const Shape& sh);   // the hidden vector fits the router kernel's LDS
 
 // h[i, :] = silu(W1 x) * (W3 x) for the k selected experts of ONE token.  hbuf: fp32 [k, F].
 hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,

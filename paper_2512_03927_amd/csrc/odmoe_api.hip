@@ -802,7 +802,13 @@ static int decode_step_impl(odmoe_layer_t* h, const void* x_dev, void* y_dev,
     return ODMOE_OK;
   };
 
-  const void* cur = x_dev;
+  // Between stacked layers the glue x_{l+1} = rmsnorm(x_l + y_l) runs at the head of layer l+1's
+  // router kernel (one launch fewer per layer; the same bits as the stand-alone glue kernel, which
+  // still closes the last layer and serves hidden sizes too long for the router's LDS).
+  const bool fuse_glue = h->cfg.glue && route_glue_fusable(h->sh);
+  const void* cur = x_dev;          // x_l: the input of layer l
+  const void* pend_x = nullptr;     // glue still to be done before layer l: x_{l-1} ...
+  const void* pend_y = nullptr;     // ... and y_{l-1}
   for (int l = 0; l < L; ++l) {
     const bool last = (l == L - 1);
     int32_t* idx_l = h->idx_dev + (size_t)l * k;
@@ -812,9 +818,13 @@ static int decode_step_impl(odmoe_layer_t* h, const void* x_dev, void* y_dev,
       if ((rc = run_actions())) return rc;
     }
     if (timed) HIP_TRY(hipEventRecord(TE(l, 0), h->compute));
+    void* x_made = pend_x ? h->xbuf[(l - 1) & 1] : nullptr;   // where the pending glue puts x_l
     HIP_TRY(launch_route_topk(h->compute, h->sh, h->router_w[l], static_cast<const float*>(h->router_b[l]),
                               cur, 1, idx_l, gate_l, h->idx_pin_dev + (size_t)l * k, h->table_dev, l * E,
-                              h->sched ? nullptr : h->eptr_dev + (size_t)l * k, &h->route_scratch));
+                              h->sched ? nullptr : h->eptr_dev + (size_t)l * k, &h->route_scratch, pend_x, pend_y,
+                              x_made));
+    if (pend_x) cur = x_made;
+    pend_x = pend_y = nullptr;
 
     ExpertSrc src{};
     int32_t slots[ODMOE_MAX_TOPK];
@@ -850,9 +860,14 @@ static int decode_step_impl(odmoe_layer_t* h, const void* x_dev, void* y_dev,
       acts.clear();
     }
     if (h->cfg.glue) {
-      void* x_next = last ? y_dev : h->xbuf[l & 1];
-      HIP_TRY(launch_glue(h->compute, h->sh, cur, y_l, x_next));
-      cur = x_next;
+      if (fuse_glue && !last) {
+        pend_x = cur;      // done by the next layer's router kernel
+        pend_y = y_l;
+      } else {
+        void* x_next = last ? y_dev : h->xbuf[l & 1];
+        HIP_TRY(launch_glue(h->compute, h->sh, cur, y_l, x_next));
+        cur = x_next;
+      }
     } else {
       cur = y_l;
     }

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(1024) void sort_slots_kernel(const int32_t* __restr
       const int e = order[p];
       const int nch = (cnt[e] + BMX - 1) / BMX;
       // rows split evenly over the chunks, rounded up to whole 32-row MFMA tiles (the number of
-      // chunks stays nch: (nch - 1) * 256 < cnt)
+      // chunks stays nch: per <= BMX, and (nch - 1) * per < cnt because (nch - 1) * BMX < cnt)
       const int per = nch ? ((cnt[e] + nch - 1) / nch + 31) & ~31 : 0;
       const int first = nt;
       for (int m0 = 0; m0 < cnt[e]; m0 += per) {
@@ -190,7 +190,7 @@ struct GemmArgs {
   int table_off;
   const void* expert_override;  // when set: the weights of every chunk of this launch (one expert)
   int tile_first;               // first chunk-list entry of this launch
-  size_t b_off[2];            // element offsets of the two 64-row halves' matrix starts
+  size_t b_off[2];            // element offsets of the matrices the two 128-row halves of the tile come from
   int b_row[2];               // first weight row of each half relative to n0
   const int32_t* tiles;
   const int32_t* n_tiles;
