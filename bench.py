@@ -110,6 +110,8 @@ def main() -> int:
                     help="size of the plain read/copy probe that measures the HBM and host-link ceilings (0 = skip)")
     ap.add_argument("--sep-iters", type=int, default=32,
                     help="emulated decode iterations with a quantised shadow stack supplying hints (0 = skip)")
+    ap.add_argument("--int8-passes", type=int, default=3,
+                    help="timed passes over the tokens with the layer's experts held as int8 codes (0 = skip)")
     ap.add_argument("--no-prefill-from-host", action="store_true",
                     help="skip the prefill run that streams the experts from host memory")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
@@ -533,9 +535,10 @@ def main() -> int:
     # ---- the shadow model's side (Sections 1, 3.2): int8 experts on the Mixtral-shaped layer (the cost
     # of the quantised copy), and the emulated predictor on a small stack (the recall it gives)
     sep = None
-    if args.sep_iters > 0:
+    if args.sep_iters > 0 or args.int8_passes > 0:
         from paper_2512_03927_amd import shadow
         sep = {}
+    if args.int8_passes > 0:
         with shadow.shadow_stack(cfg, [layer], "int8") as q8:
             Xq = harness.to_device(X_np)
             Yq = torch.empty_like(Xq)
@@ -544,12 +547,13 @@ def main() -> int:
                     B.odmoe_decode_step(q8.handle, Xq[t], Yq[t], None, None, None)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            for _ in range(3):
+            for _ in range(args.int8_passes):
                 for t in range(T):
                     B.odmoe_decode_step(q8.handle, Xq[t], Yq[t], None, None, None)
             torch.cuda.synchronize()
-            el8 = (time.perf_counter() - t1) / 3
-            r_us, u_us, d_us = B.odmoe_time_decode_kernels(q8.handle, 0, Xq, T, 2)
+            el8 = (time.perf_counter() - t1) / args.int8_passes
+            r_us, u_us, d_us = (0.0, 1.0, 1.0) if args.no_kernel_pass else \
+                B.odmoe_time_decode_kernels(q8.handle, 0, Xq, T, 2)
             ub8 = cfg.top_k * (2 * cfg.hidden * cfg.ffn + 8 * cfg.ffn)            # codes + scales of W1, W3
             db8 = cfg.top_k * (cfg.hidden * cfg.ffn + 4 * cfg.hidden)
             sep["int8_layer"] = {"workload": cfg.name + " with int8 experts (per-row scales)", "tokens": T,
@@ -563,6 +567,7 @@ def main() -> int:
                                  "route_us": round(r_us, 2)}
             del Xq, Yq
         log(f"[bench] int8 experts: {sep['int8_layer']}")
+    if args.sep_iters > 0:
         cs = synth.MoEConfig("sep-h1024-f2048-e8-k2-16L", 1024, 2048, 8, 2, n_layers=16, n_slots=4,
                              dtype="bf16", n_tokens=1, glue=1, seed=7)
         layers_s = [synth.layer_weights(cs, l) for l in range(cs.n_layers)]
