@@ -167,6 +167,52 @@ def test_int8_stack_cacheless_and_resident_agree_and_move_half_the_bytes(H):
                 assert np.max(np.abs(O.widen(H.from_device(y_c)) - ref)) <= BF16_REL * np.max(np.abs(ref))
 
 
+def test_int8_experts_in_place_from_host_memory_and_through_the_static_entry_point(H):
+    """The int8 expert format on the other routes into the same kernels: read in place from
+    pinned host memory (n_slots = 0, host pointers) and through odmoe_expert_ffn_static; both give
+    the bits of the resident int8 handle."""
+    import torch
+    from paper_2512_03927_amd import binding as B
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", 528, 1040, 8, 2, dtype="bf16", n_tokens=3, seed=65)
+    layer = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    with shadow.shadow_stack(cfg, [layer], "int8") as res:
+        routers, biases, experts = res._keep
+        x = H.to_device(X)
+        idx, gate = res.route(0, x)
+        y_res = H.from_device(res.ffn(0, idx, gate, x))
+        pinned = [[torch.empty(e.shape, dtype=e.dtype, pin_memory=True).copy_(e) for e in ex] for ex in experts]
+        with H.MoEStack(cfg, device_buffers=(routers, biases, pinned), unique_layers=1,
+                        expert_quant=B.ODMOE_Q_INT8_ROW) as host:
+            y_host = H.from_device(host.ffn(0, idx, gate, x))
+            assert np.array_equal(y_host, y_res)
+        table = torch.tensor([e.data_ptr() for e in experts[0]], dtype=torch.int64, device="cuda:0")
+        c = B.odmoe_config(cfg.hidden, cfg.ffn, cfg.n_experts, cfg.top_k, 1, 0, B.ODMOE_BF16, 0, B.ODMOE_Q_INT8_ROW)
+        y_static = torch.zeros_like(x)
+        B.odmoe_expert_ffn_static(c, table, idx, gate, x, cfg.n_tokens, y_static, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.from_device(y_static), y_res)
+
+
+def test_sep_emulate_refuses_stacks_that_do_not_match(H):
+    from paper_2512_03927_amd import binding as B
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", 64, 64, 4, 2, n_layers=2, n_slots=2, dtype="bf16", n_tokens=1, glue=1, seed=67)
+    layers = [synth.layer_weights(cfg, l) for l in range(2)]
+    x0 = H.to_device(synth.tokens(cfg)[0])
+    with H.MoEStack(cfg, layers) as main, H.MoEStack(cfg.small(n_layers=1), layers[:1]) as short, \
+            H.MoEStack(cfg, layers) as cacheless_shadow, shadow.shadow_stack(cfg, layers, "int8") as sh:
+        for bad in (short, cacheless_shadow):
+            with pytest.raises(B.OdmoeError) as ei:
+                shadow.emulate(main, bad, x0, 2, True)
+            assert ei.value.code == B.ODMOE_EINVAL
+        rec, x_end, _, _ = shadow.emulate(main, sh, x0, 0, True)          # zero iterations: main's input comes back
+        assert rec == [] and np.array_equal(H.from_device(x_end), H.from_device(x0))
+        rec, _, _, _ = shadow.emulate(main, sh, x0, 3, False)
+        assert len(rec) == 3 and all(0.0 <= r <= 1.0 for r in rec)
+
+
 def test_shadow_stack_hints(H):
     from paper_2512_03927_amd import shadow
     cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=8, n_slots=4, dtype="bf16", n_tokens=1, glue=1, seed=41)
