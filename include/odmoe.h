@@ -114,12 +114,14 @@ typedef struct {
 typedef struct {
   /* kernel / copy times are HIP-event times summed over the layers of one call; they are 0
      unless timing was asked for (see odmoe_decode_step) */
-  float t_route_ms;    /* router GEMV + top-k gate kernel */
+  float t_route_ms;    /* router GEMV + top-k gate kernel; between stacked layers it starts with the
+                          previous layer's glue (one kernel), whose time is therefore counted here */
   float t_load_ms;     /* host->HBM expert copies: time during which at least one copy was in
                           flight (copies on different copy streams overlap) */
   float t_ffn_up_ms;   /* w1/w3 GEMV + SiLU gate kernel */
   float t_ffn_down_ms; /* w2 GEMV + weighted combine kernel */
-  float t_glue_ms;     /* inter-layer glue kernel */
+  float t_glue_ms;     /* stand-alone glue kernel: after the last layer, and between layers only
+                          when the hidden vector does not fit the router kernel's LDS (32 KB) */
   float t_step_ms;     /* wall time of the call, host clock */
   uint64_t h2d_bytes; /* bytes copied host->HBM by this call */
   uint64_t loads;     /* expert loads issued by this call (cacheless: n_layers*top_k + reloads) */

@@ -992,7 +992,10 @@ static int sep_emulate_impl(odmoe_layer_t* main_stack, odmoe_layer_t* shadow, co
   const int L = m.n_layers, k = m.top_k;
   const size_t row = (size_t)m.hidden * main_stack->esize;
   char* buf = nullptr;   // four state vectors: main in / out, shadow in / out
-  HIP_TRY(hipMalloc((void**)&buf, 4 * row));
+  if (hipMalloc((void**)&buf, 4 * row) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(ODMOE_ENOMEM, "no device memory for %zu bytes of state", 4 * row);
+  }
   std::vector<int32_t> pred((size_t)L * k), used((size_t)L * k);
   using clk = std::chrono::steady_clock;
   double t_shadow = 0.0, t_main = 0.0;
