@@ -139,6 +139,37 @@ def test_int8_expert_layer_matches_oracle_on_dequantised_weights(H, Hd, F, E, k,
             assert np.array_equal(H.from_device(yt), yn[t]) and np.array_equal(idx_t[0], idx_ref)
 
 
+def _random_q8_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        E = int(rng.integers(1, 25))
+        out.append((16 * int(rng.integers(1, 129)), 16 * int(rng.integers(1, 129)), E,
+                    int(rng.integers(1, min(E, 4) + 1)), "bf16" if rng.random() < 0.6 else "f32"))
+    return out
+
+
+@pytest.mark.parametrize("Hd,F,E,k,dtype", _random_q8_shapes(12, 808))
+def test_int8_expert_layer_random_small_shapes(H, Hd, F, E, k, dtype):
+    """Seeded random shapes (hidden and ffn any multiple of 16 up to 2048, 1-24 experts): ragged
+    last chunks, every column-slice / expert-group split of the w2 kernel, both activation dtypes."""
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=2, router_bias=bool(E % 2), seed=Hd + F)
+    layer = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Wg_s, b, ex_s = _oracle_int8_layer(cfg, layer)
+    with shadow.shadow_stack(cfg, [layer], "int8") as st:
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        yn = H.from_device(st.ffn(0, idx, gate, x))
+        for t in range(cfg.n_tokens):
+            y_ref, idx_ref, g_ref = O.moe_layer(X[t], Wg_s, b, ex_s, k)
+            assert np.array_equal(idx.cpu().numpy()[t], idx_ref)
+            assert np.max(np.abs(gate.cpu().numpy()[t].astype(np.float64) - g_ref)) <= 1e-6
+            err = np.max(np.abs(O.widen(yn[t]) - y_ref))
+            assert err <= (1e-4 if dtype == "f32" else ONE_BF16_ROUNDING * np.max(np.abs(y_ref))), (t, err)
+
+
 def test_int8_stack_cacheless_and_resident_agree_and_move_half_the_bytes(H):
     """int8 experts through the slot pool: the same bits as resident, and each load is the int8
     expert's size (half of bf16 plus the scales)."""
