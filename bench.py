@@ -111,7 +111,7 @@ def main() -> int:
     ap.add_argument("--sep-iters", type=int, default=32,
                     help="emulated decode iterations with a quantised shadow stack supplying hints (0 = skip)")
     ap.add_argument("--int8-passes", type=int, default=3,
-                    help="timed passes over the tokens with the layer's experts held as int8 codes (0 = skip)")
+                    help="timed passes over the tokens with the layer's experts held as int8 / 4-bit codes (0 = skip)")
     ap.add_argument("--no-prefill-from-host", action="store_true",
                     help="skip the prefill run that streams the experts from host memory")
     ap.add_argument("--no-kernel-pass", action="store_true", help="skip the HIP-event pass (for profilers)")
@@ -538,8 +538,8 @@ def main() -> int:
     if args.sep_iters > 0 or args.int8_passes > 0:
         from paper_2512_03927_amd import shadow
         sep = {}
-    if args.int8_passes > 0:
-        with shadow.shadow_stack(cfg, [layer], "int8") as q8:
+    for qkind in (("int8", "int4") if args.int8_passes > 0 else ()):
+        with shadow.shadow_stack(cfg, [layer], qkind) as q8:
             Xq = harness.to_device(X_np)
             Yq = torch.empty_like(Xq)
             for _ in range(2):
@@ -554,19 +554,30 @@ def main() -> int:
             el8 = (time.perf_counter() - t1) / args.int8_passes
             r_us, u_us, d_us = (0.0, 1.0, 1.0) if args.no_kernel_pass else \
                 B.odmoe_time_decode_kernels(q8.handle, 0, Xq, T, 2)
-            ub8 = cfg.top_k * (2 * cfg.hidden * cfg.ffn + 8 * cfg.ffn)            # codes + scales of W1, W3
-            db8 = cfg.top_k * (cfg.hidden * cfg.ffn + 4 * cfg.hidden)
-            sep["int8_layer"] = {"workload": cfg.name + " with int8 experts (per-row scales)", "tokens": T,
-                                 "tokens_per_s": round(T / el8, 1),
-                                 "speedup_over_bf16": round(T / el8 / tokens_per_s, 3),
-                                 "expert_bytes": q8.expert_bytes, "bytes_vs_bf16": round(q8.expert_bytes / cfg.expert_bytes, 4),
-                                 "ffn_up_us": round(u_us, 2), "ffn_up_GBps": round(ub8 / u_us / 1e3, 1),
-                                 "ffn_up_frac_of_hbm_peak": round(ub8 / u_us / 1e3 / HBM_PEAK_GBPS, 4),
-                                 "ffn_down_us": round(d_us, 2), "ffn_down_GBps": round(db8 / d_us / 1e3, 1),
-                                 "ffn_down_frac_of_hbm_peak": round(db8 / d_us / 1e3 / HBM_PEAK_GBPS, 4),
-                                 "route_us": round(r_us, 2)}
+            hf = cfg.hidden * cfg.ffn
+            if qkind == "int8":      # codes + one scale per row
+                ub8, db8 = cfg.top_k * (2 * hf + 8 * cfg.ffn), cfg.top_k * (hf + 4 * cfg.hidden)
+                what = "int8 experts (a scale per weight row)"
+            else:                    # packed codes + one scale per group of 64
+                ub8, db8 = cfg.top_k * (hf + 8 * hf // 64), cfg.top_k * (hf // 2 + 4 * hf // 64)
+                what = "4-bit experts (a scale per group of 64)"
+            sep[qkind + "_layer"] = {"workload": cfg.name + " with " + what, "tokens": T,
+                                     "tokens_per_s": round(T / el8, 1),
+                                     "speedup_over_bf16": round(T / el8 / tokens_per_s, 3),
+                                     "expert_bytes": q8.expert_bytes,
+                                     "bytes_vs_bf16": round(q8.expert_bytes / cfg.expert_bytes, 4),
+                                     "ffn_up_us": round(u_us, 2), "ffn_up_GBps": round(ub8 / u_us / 1e3, 1),
+                                     "ffn_up_frac_of_hbm_peak": round(ub8 / u_us / 1e3 / HBM_PEAK_GBPS, 4),
+                                     "ffn_down_us": round(d_us, 2), "ffn_down_GBps": round(db8 / d_us / 1e3, 1),
+                                     "ffn_down_frac_of_hbm_peak": round(db8 / d_us / 1e3 / HBM_PEAK_GBPS, 4),
+                                     "route_us": round(r_us, 2)}
+            if qkind == "int4":
+                # bound by the conversion arithmetic, not the weight stream: about 2.4 vector
+                # instructions per weight (mask, byte -> fp32, FMA) against 256 CUs x 64 lanes x 2.4 GHz
+                ops = 2.4 * cfg.top_k * 3 * hf
+                sep[qkind + "_layer"]["valu_frac_of_peak"] = round(ops / ((u_us + d_us) * 1e-6) / (256 * 64 * 2.4e9), 3)
             del Xq, Yq
-        log(f"[bench] int8 experts: {sep['int8_layer']}")
+        log(f"[bench] {qkind} experts: {sep[qkind + '_layer']}")
     if args.sep_iters > 0:
         cs = synth.MoEConfig("sep-h1024-f2048-e8-k2-16L", 1024, 2048, 8, 2, n_layers=16, n_slots=4,
                              dtype="bf16", n_tokens=1, glue=1, seed=7)

@@ -36,8 +36,9 @@
  *     bf16 is the upper 16 bits of an fp32 (round-to-nearest-even).
  *   - One expert is ONE contiguous buffer:  W1[F,H] | W3[F,H] | W2[H,F]   (3*H*F elements).
  *   - hidden and ffn must be multiples of 8; 1 <= top_k <= min(n_experts, 8); n_experts <= 1024.
- *   - Experts may instead be int8 codes with a scale per weight row (odmoe_config.expert_quant):
- *     the quantised shadow model of Sections 1 and 3.2, which reads half the bytes per token.
+ *   - Experts may instead be int8 codes with a scale per weight row, or packed 4-bit codes with a
+ *     scale per group of 64 (odmoe_config.expert_quant): the quantised shadow model of Sections 1
+ *     and 3.2, which reads a half resp. 0.28 of the bytes per token.
  *   - The caller owns every buffer it passes in; weight buffers must outlive the handle.
  *     Streams are borrowed (never destroyed here).  The library owns its slot pool, scratch
  *     buffers, events and, if no copy stream was given, its copy streams.
@@ -101,14 +102,18 @@ typedef struct {
                         (any address the GPU can read will do, see "Experts read in place") */
   int32_t dtype;     /* odmoe_dtype */
   int32_t glue;      /* 0: x_{l+1} = y_l ; 1: x_{l+1} = rmsnorm(x_l + y_l) between stacked layers */
-  int32_t expert_quant; /* odmoe_quant of the expert buffers.  ODMOE_Q_NONE: weights in dtype.
-                        ODMOE_Q_INT8_ROW (a shadow model's experts): one expert is
-                          codes W1[F,H] | W3[F,H] | W2[H,F] (one byte each), then fp32 scales
-                          s1[F] | s3[F] | s2[H]
-                        as odmoe_quantize_expert writes it; x, y and the router stay in dtype, the
-                        GEMVs dequantise in registers and accumulate in fp32.  hidden and ffn must
-                        be multiples of 16, hidden <= 8192, and batches run token by token (no
-                        grouped GEMM).  ODMOE_Q_INT4_G64 is not an expert format. */
+  int32_t expert_quant; /* odmoe_quant of the expert buffers (a shadow model's experts; x, y and the
+                        router stay in dtype, the GEMVs dequantise in registers and accumulate in
+                        fp32, batches run token by token: no grouped GEMM).
+                        ODMOE_Q_NONE: weights in dtype.
+                        ODMOE_Q_INT8_ROW: codes W1[F,H] | W3[F,H] | W2[H,F] (one byte each), then
+                          fp32 scales s1[F] | s3[F] | s2[H].  hidden and ffn multiples of 16,
+                          hidden <= 8192.
+                        ODMOE_Q_INT4_G64: codes packed two per byte (element 2j in the low nibble of
+                          byte j) W1[F][H/2] | W3[F][H/2] | W2[H][F/2], then fp32 scales, one per
+                          group of 64 weights of a row, s1[F][H/64] | s3[F][H/64] | s2[H][F/64].
+                          hidden and ffn multiples of 64, hidden <= 8192.
+                        Both as odmoe_quantize_expert writes them. */
 } odmoe_config;
 
 typedef struct {
@@ -259,7 +264,8 @@ int odmoe_expert_ffn_static(const odmoe_config* cfg, const void* const* expert_t
                             int32_t n_tokens, void* y_dev, void* stream);
 
 /* Bytes of one expert buffer as a handle made from cfg expects it: 3*H*F elements of dtype, or for
- * ODMOE_Q_INT8_ROW 3*H*F code bytes + 4*(2*F + H) bytes of scales.  0 for a NULL or invalid cfg. */
+ * ODMOE_Q_INT8_ROW 3*H*F code bytes + 4*(2*F + H) bytes of scales, for ODMOE_Q_INT4_G64 3*H*F/2
+ * code bytes + 4*(3*H*F/64) bytes of scales.  0 for a NULL or invalid cfg. */
 uint64_t odmoe_expert_bytes(const odmoe_config* cfg);
 
 /*
@@ -276,10 +282,12 @@ uint64_t odmoe_expert_bytes(const odmoe_config* cfg);
 int odmoe_quantize(const void* w_dev, int32_t dtype, int64_t rows, int64_t cols, int32_t kind,
                    uint8_t* code_dev, float* scale_dev, void* dequant_dev, void* stream);
 
-/* One stored expert W1[F,H] | W3[F,H] | W2[H,F] (cfg->dtype, device) into the ODMOE_Q_INT8_ROW
- * expert buffer described at odmoe_config (dst_dev: odmoe_expert_bytes of the quantised config,
- * device).  cfg->expert_quant is ignored.  Asynchronous on `stream`. */
-int odmoe_quantize_expert(const odmoe_config* cfg, const void* expert_dev, void* dst_dev, void* stream);
+/* One stored expert W1[F,H] | W3[F,H] | W2[H,F] (cfg->dtype, device) into the expert buffer of
+ * format `kind` (ODMOE_Q_INT8_ROW or ODMOE_Q_INT4_G64) described at odmoe_config; dst_dev: device,
+ * odmoe_expert_bytes of the config with expert_quant = kind.  The codes and scales are those of
+ * odmoe_quantize on the three matrices.  cfg->expert_quant is ignored.  Asynchronous on `stream`. */
+int odmoe_quantize_expert(const odmoe_config* cfg, int32_t kind, const void* expert_dev, void* dst_dev,
+                          void* stream);
 
 /*
  * Scaled emulative prediction, emulated on one GPU (Sections 1, 3.2): `shadow` (a stack of the

@@ -75,7 +75,7 @@ def lib() -> C.CDLL:
     L.odmoe_expert_bytes.argtypes = [C.POINTER(odmoe_config)]
     L.odmoe_expert_bytes.restype = u64
     L.odmoe_quantize.argtypes = [vp, i32, C.c_int64, C.c_int64, i32, vp, vp, vp, vp]
-    L.odmoe_quantize_expert.argtypes = [C.POINTER(odmoe_config), vp, vp, vp]
+    L.odmoe_quantize_expert.argtypes = [C.POINTER(odmoe_config), i32, vp, vp, vp]
     L.odmoe_sep_emulate.argtypes = [vp, vp, vp, i32, i32, C.POINTER(C.c_float), vp, C.POINTER(C.c_float),
                                     C.POINTER(C.c_float)]
     L.odmoe_pinned_alloc.argtypes = [u64, C.POINTER(vp)]
@@ -191,8 +191,8 @@ def odmoe_quantize(w_dev, dtype: int, rows: int, cols: int, kind: int, code_dev=
                                 _ptr(dequant_dev), stream))
 
 
-def odmoe_quantize_expert(cfg: odmoe_config, expert_dev, dst_dev, stream: Optional[int] = None) -> None:
-    _check(lib().odmoe_quantize_expert(C.byref(cfg), _ptr(expert_dev), _ptr(dst_dev), stream))
+def odmoe_quantize_expert(cfg: odmoe_config, kind: int, expert_dev, dst_dev, stream: Optional[int] = None) -> None:
+    _check(lib().odmoe_quantize_expert(C.byref(cfg), kind, _ptr(expert_dev), _ptr(dst_dev), stream))
 
 
 def odmoe_sep_emulate(main: int, shadow: int, x0_dev, n_iter: int, aligned: bool, x_final_dev=None):

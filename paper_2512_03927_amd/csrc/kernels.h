@@ -29,7 +29,8 @@ struct Shape {
   // runs lose 4-7 % of its rate.
   int32_t host_link = 0;
   // odmoe_quant of the expert buffers: 0 = weights in `dtype`; ODMOE_Q_INT8_ROW = int8 codes with
-  // one fp32 scale per weight row (x, y and the router stay in `dtype`).
+  // one fp32 scale per weight row; ODMOE_Q_INT4_G64 = packed 4-bit codes with one fp32 scale per
+  // group of 64 (x, y and the router stay in `dtype`).
   int32_t quant = 0;
 };
 
@@ -74,6 +75,18 @@ hipError_t launch_ffn_up_q8(hipStream_t s, const Shape& sh, const ExpertSrc& src
                             const void* x, float* hbuf);
 hipError_t launch_ffn_down_q8(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
                               const float* gate, const float* hbuf, void* y);
+
+// ... and over 4-bit expert buffers (codes packed two per byte W1 | W3 | W2, then one fp32 scale
+// per group of 64 weights s1[F][H/64] | s3[F][H/64] | s2[H][F/64]); sh.quant == ODMOE_Q_INT4_G64.
+bool q4_supported(const Shape& sh);   // H and F multiples of 64, H <= 8192
+hipError_t launch_ffn_up_q4(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                            const void* x, float* hbuf);
+hipError_t launch_ffn_down_q4(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                              const float* gate, const float* hbuf, void* y);
+// w[rows, cols] (dtype, cols a multiple of 64) -> packed 4-bit codes [rows, cols/2] and scales
+// [rows, cols/64]: the codes of launch_quantize(ODMOE_Q_INT4_G64), two per byte.
+hipError_t launch_quantize_pack4(hipStream_t s, const void* w, int32_t dtype, int64_t rows, int64_t cols,
+                                 uint8_t* packed, float* scale);
 
 // Symmetric absmax quantisation of w[rows, cols] (dtype) on the device; kind is an odmoe_quant.
 // code (u8, offset-binary), scale (fp32, per row or per group of 64) and deq (code * scale rounded

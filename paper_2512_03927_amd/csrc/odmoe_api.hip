@@ -57,6 +57,7 @@ size_t dtype_size(int32_t dt) { return dt == ODMOE_F32 ? 4 : 2; }
 size_t expert_bytes_of(const odmoe_config& c) {
   const size_t hf = (size_t)c.hidden * c.ffn;
   if (c.expert_quant == ODMOE_Q_INT8_ROW) return 3 * hf + sizeof(float) * (2 * (size_t)c.ffn + c.hidden);
+  if (c.expert_quant == ODMOE_Q_INT4_G64) return 3 * hf / 2 + sizeof(float) * (3 * hf / 64);
   return 3 * hf * dtype_size(c.dtype);
 }
 
@@ -121,8 +122,12 @@ int validate_cfg(const odmoe_config* c) {
     return fail(ODMOE_EINVAL, "n_slots %d must be 0 (resident) or >= top_k", c->n_slots);
   if (c->dtype != ODMOE_F32 && c->dtype != ODMOE_BF16) return fail(ODMOE_EINVAL, "bad dtype %d", c->dtype);
   if (c->glue != 0 && c->glue != 1) return fail(ODMOE_EINVAL, "bad glue %d", c->glue);
-  if (c->expert_quant != ODMOE_Q_NONE && c->expert_quant != ODMOE_Q_INT8_ROW)
-    return fail(ODMOE_EINVAL, "expert_quant %d: experts are stored in dtype (0) or as int8 rows (1)", c->expert_quant);
+  if (c->expert_quant != ODMOE_Q_NONE && c->expert_quant != ODMOE_Q_INT8_ROW && c->expert_quant != ODMOE_Q_INT4_G64)
+    return fail(ODMOE_EINVAL, "expert_quant %d: experts are stored in dtype (0), as int8 rows (1) or 4-bit groups (2)",
+                c->expert_quant);
+  if (c->expert_quant == ODMOE_Q_INT4_G64 && (c->hidden % 64 || c->ffn % 64 || c->hidden > 8192))
+    return fail(ODMOE_EINVAL, "4-bit experts need hidden (%d) and ffn (%d) to be multiples of 64 and hidden <= 8192",
+                c->hidden, c->ffn);
   if (c->expert_quant == ODMOE_Q_INT8_ROW && (c->hidden % 16 || c->ffn % 16 || c->hidden > 8192))
     return fail(ODMOE_EINVAL, "int8 experts need hidden (%d) and ffn (%d) to be multiples of 16 and hidden <= 8192",
                 c->hidden, c->ffn);
@@ -278,22 +283,32 @@ int odmoe_quantize(const void* w_dev, int32_t dtype, int64_t rows, int64_t cols,
   return ODMOE_OK;
 }
 
-int odmoe_quantize_expert(const odmoe_config* cfg, const void* expert_dev, void* dst_dev, void* stream) {
+int odmoe_quantize_expert(const odmoe_config* cfg, int32_t kind, const void* expert_dev, void* dst_dev,
+                          void* stream) {
   if (!cfg) return fail(ODMOE_EINVAL, "cfg is NULL");
+  if (kind != ODMOE_Q_INT8_ROW && kind != ODMOE_Q_INT4_G64) return fail(ODMOE_EINVAL, "bad quantisation kind %d", kind);
   odmoe_config qc = *cfg;
-  qc.expert_quant = ODMOE_Q_INT8_ROW;
+  qc.expert_quant = kind;
   int rc = validate_cfg(&qc);
   if (rc) return rc;
   if (!expert_dev || !dst_dev) return fail(ODMOE_EINVAL, "expert / dst is NULL");
   const size_t H = cfg->hidden, F = cfg->ffn, hf = H * F, es = dtype_size(cfg->dtype);
   const char* src = static_cast<const char*>(expert_dev);
   uint8_t* code = static_cast<uint8_t*>(dst_dev);
-  float* scale = reinterpret_cast<float*>(code + 3 * hf);
   hipStream_t s = static_cast<hipStream_t>(stream);
-  HIP_TRY(launch_quantize(s, src, cfg->dtype, F, H, ODMOE_Q_INT8_ROW, code, scale, nullptr));                       // W1
-  HIP_TRY(launch_quantize(s, src + hf * es, cfg->dtype, F, H, ODMOE_Q_INT8_ROW, code + hf, scale + F, nullptr));    // W3
-  HIP_TRY(launch_quantize(s, src + 2 * hf * es, cfg->dtype, H, F, ODMOE_Q_INT8_ROW, code + 2 * hf, scale + 2 * F,
-                          nullptr));                                                                                   // W2
+  const int dt = cfg->dtype;
+  if (kind == ODMOE_Q_INT8_ROW) {
+    float* scale = reinterpret_cast<float*>(code + 3 * hf);
+    HIP_TRY(launch_quantize(s, src, dt, F, H, kind, code, scale, nullptr));                             // W1
+    HIP_TRY(launch_quantize(s, src + hf * es, dt, F, H, kind, code + hf, scale + F, nullptr));          // W3
+    HIP_TRY(launch_quantize(s, src + 2 * hf * es, dt, H, F, kind, code + 2 * hf, scale + 2 * F, nullptr));  // W2
+  } else {
+    float* scale = reinterpret_cast<float*>(code + 3 * hf / 2);
+    const size_t ng = hf / 64;   // groups (= scales) per matrix
+    HIP_TRY(launch_quantize_pack4(s, src, dt, F, H, code, scale));                                       // W1
+    HIP_TRY(launch_quantize_pack4(s, src + hf * es, dt, F, H, code + hf / 2, scale + ng));               // W3
+    HIP_TRY(launch_quantize_pack4(s, src + 2 * hf * es, dt, H, F, code + hf, scale + 2 * ng));           // W2
+  }
   return ODMOE_OK;
 }
 

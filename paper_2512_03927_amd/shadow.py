@@ -7,13 +7,13 @@ stack on the same GPU, built from the full stack's stored weights by the library
 
   'bf16'  an identical copy (the predictor that is always right)
   'int8'  experts as int8 codes with a scale per weight row, read by the int8 GEMV kernels (half
-          the bytes per token); the router quantised the same way and held dequantised in the
-          storage dtype (it is tiny)
-  'int4'  4 bits per weight in groups of 64, held dequantised in the storage dtype (there is no
-          4-bit GEMV: this copy shows the routing drift only, not the cost)
+          the bytes per token)
+  'int4'  experts as packed 4-bit codes with a scale per group of 64 weights, read by the 4-bit
+          GEMV kernels (0.28 of the bytes per token)
 
-This module only moves buffers and calls the library (marshalling); `emulate` is
-`odmoe_sep_emulate`.
+In both quantised copies the router is quantised the same way and held dequantised in the storage
+dtype (it is tiny).  This module only moves buffers and calls the library (marshalling);
+`emulate` is `odmoe_sep_emulate`.
 """
 from __future__ import annotations
 
@@ -23,6 +23,8 @@ import torch
 
 from . import binding as B
 from . import harness, synth
+
+QUANT_OF_KIND = {"int8": B.ODMOE_Q_INT8_ROW, "int4": B.ODMOE_Q_INT4_G64}
 
 
 def _dtype_code(cfg: synth.MoEConfig) -> int:
@@ -38,11 +40,13 @@ def shadow_stack(cfg: synth.MoEConfig, layers: Sequence, kind: str, device: str 
     if kind == "bf16":
         return harness.MoEStack(rcfg, list(layers), device=device)
     dt, td = _dtype_code(cfg), harness.torch_dtype(cfg.dtype)
-    qkind = B.ODMOE_Q_INT8_ROW if kind == "int8" else B.ODMOE_Q_INT4_G64
+    qkind = QUANT_OF_KIND[kind]
     H, F, E = cfg.hidden, cfg.ffn, cfg.n_experts
     stream = torch.cuda.current_stream(torch.device(device)).cuda_stream
-    c = B.odmoe_config(H, F, E, cfg.top_k, 1, 0, dt, 0, B.ODMOE_Q_INT8_ROW)
+    c = B.odmoe_config(H, F, E, cfg.top_k, 1, 0, dt, 0, qkind)
     q_bytes = B.odmoe_expert_bytes(c)
+    if q_bytes == 0:
+        raise ValueError(f"{kind} experts do not take this shape: {B.odmoe_last_error()}")
     routers, biases, experts_all = [], [], []
     for (Wg, b, experts) in layers:
         src = harness.to_device(Wg, device)
@@ -53,21 +57,13 @@ def shadow_stack(cfg: synth.MoEConfig, layers: Sequence, kind: str, device: str 
         ex: List[torch.Tensor] = []
         for flat in experts:
             src = harness.to_device(flat, device)
-            if kind == "int8":
-                dst = torch.empty(q_bytes, dtype=torch.uint8, device=device)
-                B.odmoe_quantize_expert(c, src, dst, stream)
-            else:
-                dst = torch.empty(3 * H * F, dtype=td, device=device)
-                es = dst.element_size()
-                for part, (rows, cols) in enumerate(((F, H), (F, H), (H, F))):
-                    off = part * H * F * es
-                    B.odmoe_quantize(src.data_ptr() + off, dt, rows, cols, qkind, None, None, dst.data_ptr() + off, stream)
+            dst = torch.empty(q_bytes, dtype=torch.uint8, device=device)
+            B.odmoe_quantize_expert(c, qkind, src, dst, stream)
             torch.cuda.synchronize()        # src may be freed
             ex.append(dst)
         experts_all.append(ex)
     return harness.MoEStack(rcfg, device=device, device_buffers=(routers, biases, experts_all),
-                            unique_layers=len(routers),
-                            expert_quant=B.ODMOE_Q_INT8_ROW if kind == "int8" else B.ODMOE_Q_NONE)
+                            unique_layers=len(routers), expert_quant=qkind)
 
 
 def emulate(main: harness.MoEStack, shadow: harness.MoEStack, x0: torch.Tensor, n_iter: int, aligned: bool):

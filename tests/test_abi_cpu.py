@@ -50,7 +50,7 @@ def test_argument_errors_need_no_gpu():
     assert lib.odmoe_layer_init(ctypes.byref(bad), None, None, None, None, None, ctypes.byref(out)) == B.ODMOE_EINVAL
     assert "multiples of 8" in B.odmoe_last_error()
     for kw in (dict(top_k=9), dict(top_k=5), dict(n_slots=1), dict(dtype=7), dict(n_experts=0), dict(n_layers=0),
-               dict(glue=2), dict(ffn=1 << 20), dict(expert_quant=2), dict(expert_quant=1, hidden=72),
+               dict(glue=2), dict(ffn=1 << 20), dict(expert_quant=3), dict(expert_quant=2, ffn=96), dict(expert_quant=1, hidden=72),
                dict(expert_quant=1, hidden=16384)):
         base = dict(hidden=64, ffn=64, n_experts=4, top_k=2, n_layers=1, n_slots=0, dtype=0, glue=0, expert_quant=0)
         base.update(kw)
@@ -65,6 +65,8 @@ def test_argument_errors_need_no_gpu():
     assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 * 2 == 352321536
     c.expert_quant = B.ODMOE_Q_INT8_ROW
     assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 + 4 * (2 * 14336 + 4096)
+    c.expert_quant = B.ODMOE_Q_INT4_G64
+    assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 // 2 + 4 * (3 * 4096 * 14336 // 64)
     assert B.odmoe_expert_bytes(bad) == 0
     assert lib.odmoe_quantize(None, 1, 4, 64, 1, None, None, None, None) == B.ODMOE_EINVAL
     assert lib.odmoe_quantize(1, 1, 4, 100, 2, None, None, None, None) == B.ODMOE_EINVAL     # 4-bit groups of 64

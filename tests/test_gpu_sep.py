@@ -85,20 +85,97 @@ def test_device_quantiser_int4_groups_is_bit_exact(H, dtype):
     assert np.array_equal(deq, O.round_to_storage(S.dequantize_groups(q, s, 64), dtype))
 
 
-def _oracle_int8_layer(cfg, layer):
-    """(Wg', b, experts') the int8 shadow copy holds, as float64: router = stored(q * s) as the
-    device writes it, experts = q * float32(s) as the int8 GEMVs read them."""
+def _oracle_quant_layer(cfg, layer, kind="int8"):
+    """(Wg', b, experts') the quantised shadow copy holds, as float64: router = stored(q * s) as the
+    device writes it, experts = q * float32(s) as the int8 / 4-bit GEMVs read them."""
     Wg, b, experts = layer
     Hd, F = cfg.hidden, cfg.ffn
-    Wg_s = O.round_to_storage(S.shadow_matrix(O.widen(Wg), "int8"), cfg.dtype)
+    Wg_s = O.round_to_storage(S.shadow_matrix(O.widen(Wg), kind), cfg.dtype)
     ex = []
     for flat in experts:
         parts = []
         for W in O.split_expert(flat, Hd, F):
-            q, s = S.quantize_rows_int8(O.widen(W))
-            parts.append(S.dequantize_rows(q, s.astype(np.float32)))
+            if kind == "int8":
+                q, s = S.quantize_rows_int8(O.widen(W))
+                parts.append(S.dequantize_rows(q, s.astype(np.float32)))
+            else:
+                q, s = S.quantize_groups_int4(O.widen(W), 64)
+                parts.append(S.dequantize_groups(q, s.astype(np.float32).astype(np.float64), 64))
         ex.append(tuple(parts))
     return Wg_s, b, ex
+
+
+def _oracle_int8_layer(cfg, layer):
+    return _oracle_quant_layer(cfg, layer, "int8")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_packed_4bit_expert_buffer_is_bit_exact(H, dtype):
+    """odmoe_quantize_expert(ODMOE_Q_INT4_G64): two codes per byte (element 2j in the low nibble),
+    then one fp32 scale per group of 64; codes and scales equal the oracle's."""
+    import torch
+    from paper_2512_03927_amd import binding as B
+    cfg = synth.MoEConfig("t", 128, 192, 2, 1, dtype=dtype, seed=71)
+    Hd, F = cfg.hidden, cfg.ffn
+    flat = synth.expert_weights(cfg, 0, 1)
+    flat[Hd * 5:Hd * 5 + 64] = 0                                  # an all-zero group
+    c = B.odmoe_config(Hd, F, 2, 1, 1, 0, B.ODMOE_F32 if dtype == "f32" else B.ODMOE_BF16, 0, B.ODMOE_Q_INT4_G64)
+    nbytes = B.odmoe_expert_bytes(c)
+    assert nbytes == 3 * Hd * F // 2 + 4 * (3 * Hd * F // 64)
+    dst = torch.zeros(nbytes, dtype=torch.uint8, device="cuda:0")
+    B.odmoe_quantize_expert(c, B.ODMOE_Q_INT4_G64, H.to_device(flat), dst, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = dst.cpu().numpy()
+    codes, scales = raw[:3 * Hd * F // 2], raw[3 * Hd * F // 2:].view(np.float32)
+    mats = O.split_expert(flat, Hd, F)
+    c_off = s_off = 0
+    for W in mats:
+        rows, cols = W.shape
+        q, s = S.quantize_groups_int4(O.widen(W), 64)
+        packed = codes[c_off:c_off + rows * cols // 2].reshape(rows, cols // 2)
+        got = np.empty((rows, cols), np.int32)
+        got[:, 0::2] = (packed & 0x0F).astype(np.int32) - 8
+        got[:, 1::2] = (packed >> 4).astype(np.int32) - 8
+        assert np.array_equal(got, q.astype(np.int32))
+        assert np.array_equal(scales[s_off:s_off + rows * cols // 64].reshape(rows, cols // 64), s.astype(np.float32))
+        c_off += rows * cols // 2
+        s_off += rows * cols // 64
+
+
+Q4_SHAPES = [
+    (64, 64, 4, 2, "bf16"),          # the smallest shape 4-bit experts take: one group per row
+    (2048, 1408, 8, 6, "bf16"),      # the fine-grained layer shape (config 5): one chunk of 2048 weights
+    (1088, 2112, 6, 3, "bf16"),      # ragged: half-filled chunks in both GEMVs
+    (320, 576, 5, 3, "f32"),         # fp32 activations over 4-bit experts
+    (6144, 64, 4, 2, "bf16"),        # three register chunks in the w1/w3 GEMV
+    (64, 40960, 3, 2, "bf16"),       # the longest ffn vector: 20 chunks, two per wave
+    (4096, 14336, 4, 2, "bf16"),     # the Mixtral layer shape
+]
+
+
+@pytest.mark.parametrize("Hd,F,E,k,dtype", Q4_SHAPES)
+def test_4bit_expert_layer_matches_oracle_on_dequantised_weights(H, Hd, F, E, k, dtype):
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=3 if Hd * F < (1 << 24) else 2, seed=73)
+    layer = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Wg_s, b, ex_s = _oracle_quant_layer(cfg, layer, "int4")
+    with shadow.shadow_stack(cfg, [layer], "int4") as st:
+        assert st.expert_bytes == 3 * Hd * F // 2 + 4 * (3 * Hd * F // 64)
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        yn = H.from_device(st.ffn(0, idx, gate, x))
+        ids = idx.cpu().numpy()
+        for t in range(cfg.n_tokens):
+            y_ref, idx_ref, _ = O.moe_layer(X[t], Wg_s, b, ex_s, k)
+            assert np.array_equal(ids[t], idx_ref)
+            err = np.max(np.abs(O.widen(yn[t]) - y_ref))
+            if dtype == "f32":
+                assert err <= 1e-4
+            else:
+                assert err <= ONE_BF16_ROUNDING * np.max(np.abs(y_ref)), (t, err / np.max(np.abs(y_ref)))
+            yt, idx_t, _ = st.decode(x[t])
+            assert np.array_equal(H.from_device(yt), yn[t]) and np.array_equal(idx_t[0], idx_ref)
 
 
 Q8_SHAPES = [
