@@ -216,26 +216,23 @@ def test_int8_expert_layer_matches_oracle_on_dequantised_weights(H, Hd, F, E, k,
             assert np.array_equal(H.from_device(yt), yn[t]) and np.array_equal(idx_t[0], idx_ref)
 
 
-def _random_q8_shapes(n, seed):
+def _random_quant_shapes(n, seed, step):
     rng = np.random.default_rng(seed)
     out = []
     for _ in range(n):
         E = int(rng.integers(1, 25))
-        out.append((16 * int(rng.integers(1, 129)), 16 * int(rng.integers(1, 129)), E,
+        out.append((step * int(rng.integers(1, 2048 // step + 1)), step * int(rng.integers(1, 2048 // step + 1)), E,
                     int(rng.integers(1, min(E, 4) + 1)), "bf16" if rng.random() < 0.6 else "f32"))
     return out
 
 
-@pytest.mark.parametrize("Hd,F,E,k,dtype", _random_q8_shapes(12, 808))
-def test_int8_expert_layer_random_small_shapes(H, Hd, F, E, k, dtype):
-    """Seeded random shapes (hidden and ffn any multiple of 16 up to 2048, 1-24 experts): ragged
-    last chunks, every column-slice / expert-group split of the w2 kernel, both activation dtypes."""
+def _check_random_quant_shape(H, kind, Hd, F, E, k, dtype):
     from paper_2512_03927_amd import shadow
     cfg = synth.MoEConfig("t", Hd, F, E, k, dtype=dtype, n_tokens=2, router_bias=bool(E % 2), seed=Hd + F)
     layer = synth.layer_weights(cfg)
     X = synth.tokens(cfg)
-    Wg_s, b, ex_s = _oracle_int8_layer(cfg, layer)
-    with shadow.shadow_stack(cfg, [layer], "int8") as st:
+    Wg_s, b, ex_s = _oracle_quant_layer(cfg, layer, kind)
+    with shadow.shadow_stack(cfg, [layer], kind) as st:
         x = H.to_device(X)
         idx, gate = st.route(0, x)
         yn = H.from_device(st.ffn(0, idx, gate, x))
@@ -247,22 +244,35 @@ def test_int8_expert_layer_random_small_shapes(H, Hd, F, E, k, dtype):
             assert err <= (1e-4 if dtype == "f32" else ONE_BF16_ROUNDING * np.max(np.abs(y_ref))), (t, err)
 
 
-def test_int8_stack_cacheless_and_resident_agree_and_move_half_the_bytes(H):
-    """int8 experts through the slot pool: the same bits as resident, and each load is the int8
-    expert's size (half of bf16 plus the scales)."""
+@pytest.mark.parametrize("Hd,F,E,k,dtype", _random_quant_shapes(12, 808, 16))
+def test_int8_expert_layer_random_small_shapes(H, Hd, F, E, k, dtype):
+    """Seeded random shapes (hidden and ffn any multiple of 16 up to 2048, 1-24 experts): ragged
+    last chunks, every column-slice / expert-group split of the w2 kernel, both activation dtypes."""
+    _check_random_quant_shape(H, "int8", Hd, F, E, k, dtype)
+
+
+@pytest.mark.parametrize("Hd,F,E,k,dtype", _random_quant_shapes(10, 909, 64))
+def test_4bit_expert_layer_random_small_shapes(H, Hd, F, E, k, dtype):
+    """The same for packed 4-bit experts: hidden and ffn any multiple of 64 (whole groups) up to 2048."""
+    _check_random_quant_shape(H, "int4", Hd, F, E, k, dtype)
+
+
+@pytest.mark.parametrize("kind,byte_share", [("int8", 0.51), ("int4", 0.29)])
+def test_quantised_stack_cacheless_and_resident_agree_and_move_fewer_bytes(H, kind, byte_share):
+    """Quantised experts through the slot pool: the same bits as resident, and each load is the
+    quantised expert's size (int8: half of bf16 plus the row scales; 4-bit: 0.281 of bf16)."""
     import torch
-    from paper_2512_03927_amd import binding as B
     from paper_2512_03927_amd import shadow
     cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=5, n_slots=4, dtype="bf16", n_tokens=2, glue=1, seed=63)
     layers = [synth.layer_weights(cfg, l) for l in range(cfg.n_layers)]
     X = synth.tokens(cfg)
-    with shadow.shadow_stack(cfg, layers, "int8") as res:
+    with shadow.shadow_stack(cfg, layers, kind) as res:
         routers, biases, experts = res._keep
         pinned = [[torch.empty(e.shape, dtype=e.dtype, pin_memory=True).copy_(e) for e in ex] for ex in experts]
         with H.MoEStack(cfg, device_buffers=(routers, biases, pinned), unique_layers=cfg.n_layers,
-                        expert_quant=B.ODMOE_Q_INT8_ROW) as st:
-            assert st.expert_bytes < cfg.expert_bytes * 0.51
-            layers_o = [_oracle_int8_layer(cfg, l) for l in layers]
+                        expert_quant=shadow.QUANT_OF_KIND[kind]) as st:
+            assert st.expert_bytes < cfg.expert_bytes * byte_share
+            layers_o = [_oracle_quant_layer(cfg, l, kind) for l in layers]
             for t in range(cfg.n_tokens):
                 x = H.to_device(X[t])
                 y_r, idx_r, _ = res.decode(x)
@@ -275,32 +285,59 @@ def test_int8_stack_cacheless_and_resident_agree_and_move_half_the_bytes(H):
                 assert np.max(np.abs(O.widen(H.from_device(y_c)) - ref)) <= BF16_REL * np.max(np.abs(ref))
 
 
-def test_int8_experts_in_place_from_host_memory_and_through_the_static_entry_point(H):
-    """The int8 expert format on the other routes into the same kernels: read in place from
+@pytest.mark.parametrize("kind,Hd,F", [("int8", 528, 1040), ("int4", 576, 1088)])
+def test_quantised_experts_in_place_from_host_memory_and_through_the_static_entry_point(H, kind, Hd, F):
+    """The quantised expert formats on the other routes into the same kernels: read in place from
     pinned host memory (n_slots = 0, host pointers) and through odmoe_expert_ffn_static; both give
-    the bits of the resident int8 handle."""
+    the bits of the resident quantised handle."""
     import torch
     from paper_2512_03927_amd import binding as B
     from paper_2512_03927_amd import shadow
-    cfg = synth.MoEConfig("t", 528, 1040, 8, 2, dtype="bf16", n_tokens=3, seed=65)
+    cfg = synth.MoEConfig("t", Hd, F, 8, 2, dtype="bf16", n_tokens=3, seed=65)
     layer = synth.layer_weights(cfg)
     X = synth.tokens(cfg)
-    with shadow.shadow_stack(cfg, [layer], "int8") as res:
+    with shadow.shadow_stack(cfg, [layer], kind) as res:
         routers, biases, experts = res._keep
         x = H.to_device(X)
         idx, gate = res.route(0, x)
         y_res = H.from_device(res.ffn(0, idx, gate, x))
         pinned = [[torch.empty(e.shape, dtype=e.dtype, pin_memory=True).copy_(e) for e in ex] for ex in experts]
         with H.MoEStack(cfg, device_buffers=(routers, biases, pinned), unique_layers=1,
-                        expert_quant=B.ODMOE_Q_INT8_ROW) as host:
+                        expert_quant=shadow.QUANT_OF_KIND[kind]) as host:
             y_host = H.from_device(host.ffn(0, idx, gate, x))
             assert np.array_equal(y_host, y_res)
         table = torch.tensor([e.data_ptr() for e in experts[0]], dtype=torch.int64, device="cuda:0")
-        c = B.odmoe_config(cfg.hidden, cfg.ffn, cfg.n_experts, cfg.top_k, 1, 0, B.ODMOE_BF16, 0, B.ODMOE_Q_INT8_ROW)
+        c = B.odmoe_config(cfg.hidden, cfg.ffn, cfg.n_experts, cfg.top_k, 1, 0, B.ODMOE_BF16, 0,
+                           shadow.QUANT_OF_KIND[kind])
         y_static = torch.zeros_like(x)
         B.odmoe_expert_ffn_static(c, table, idx, gate, x, cfg.n_tokens, y_static, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         assert np.array_equal(H.from_device(y_static), y_res)
+
+
+@pytest.mark.parametrize("kind", ["int8", "int4"])
+def test_quantised_experts_skip_an_idx_that_is_no_expert_id(H, kind):
+    """As for experts stored in dtype: an idx entry outside [0, E) is never used as a table index,
+    and that rank adds nothing to y."""
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", 320, 576, 6, 3, dtype="bf16", n_tokens=2, seed=69)
+    layer = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    _, _, ex_s = _oracle_quant_layer(cfg, layer, kind)
+    with shadow.shadow_stack(cfg, [layer], kind) as st:
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        bad = idx.clone()
+        bad[0, 2] = 6            # E itself: the first id past the table
+        bad[1, 0] = -1
+        yb = H.from_device(st.ffn(0, bad, gate, x))
+        ids, g = idx.cpu().numpy(), gate.cpu().numpy().astype(np.float64)
+        for t, skip in ((0, 2), (1, 0)):
+            ref = np.zeros(cfg.hidden)
+            for i in range(cfg.top_k):
+                if i != skip:
+                    ref += g[t, i] * O.expert_ffn(*ex_s[ids[t, i]], X[t])
+            assert np.max(np.abs(O.widen(yb[t]) - ref)) <= ONE_BF16_ROUNDING * np.max(np.abs(ref))
 
 
 def test_sep_emulate_refuses_stacks_that_do_not_match(H):
