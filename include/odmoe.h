@@ -3,7 +3,7 @@
  * of OD-MoE (arXiv 2512.03927) on one AMD MI355X (gfx950).
  *
  * What the calls compute.  Per token and per MoE layer (paper Section 3.1: the gating
- * network "as in a standard MoE system", top-2 policy; Section 4.1: Mixtral-8x7B experts):
+ * network is the usual one of MoE models, top-2 policy; Section 4.1: Mixtral-8x7B experts):
  *
  *   logit[e] = b[e] + sum_h Wg[e,h] x[h]                  (float64 sum, rounded once to fp32)
  *   idx      = k largest logits, order (logit desc, index asc)       -- ties: lowest index wins

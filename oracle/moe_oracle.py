@@ -9,9 +9,9 @@ What the paper fixes: on-demand loading and eviction move bytes, they do not
 change the mathematics (Section 1: full precision and all expert activations
 are kept; Section 4.4: answer quality equals the fully cached model).  So the
 oracle is the plain top-k MoE layer the paper points to (Section 3.1: the
-gating network works as in a standard MoE system; top-2 policy; Section 4.1:
-Mixtral-8x7B, i.e. SwiGLU experts w1/w3/w2 and a softmax gate renormalised over
-the k selected experts).  The paper never prints these formulas; the reading
+gating network is the usual one of MoE models and is not spelled out; top-2
+policy; Section 4.1: Mixtral-8x7B, i.e. SwiGLU experts w1/w3/w2 and a softmax
+gate renormalised over the k selected experts).  The paper never prints these formulas; the reading
 taken here, per step:
 
   1. logit[e] = b[e] + sum_h Wg[e,h] x[h]        float64, then rounded once to fp32
