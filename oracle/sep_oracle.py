@@ -8,12 +8,16 @@ readings taken for the synthetic emulation are the plain symmetric absmax scheme
   int8, per weight row :  s = max|w| / 127,  q = clip(rne(w / s), -127, 127),  w' = q * s
   int4, per group of 64 consecutive weights of a row:  s = max|w| / 7,  q = clip(rne(w / s), -7, 7)
 
+  fp16: w' = the IEEE binary16 value nearest to w (ties to even), |w| clipped to 65504 first
+  (the paper's FP16 shadow of an FP32 model)
+
 (rne = round half to even; an all-zero row / group keeps scale 0 and stays zero.)  The shadow
 stack then holds w' rounded to the storage dtype.  NF4's code book is not reproduced; the 4-bit
 scheme here is uniform, so its recall is not comparable to the paper's NF4 number.
 
 Pins (tests/test_sep_cpu.py): error bound |w - w'| <= s/2, exactness on grid points, idempotence,
-zero rows, sign symmetry, hand-worked rows, and agreement of the recall bookkeeping with
+zero rows, sign symmetry, hand-worked rows, binary16 values worked by hand (ties, subnormals,
+clipping), and agreement of the recall bookkeeping with
 moe_oracle.recall.  Shares no code with the product's quantiser; tests compare the two bit for bit.
 """
 from __future__ import annotations
@@ -48,6 +52,13 @@ def quantize_groups_int4(W: np.ndarray, group: int = 64):
     return q.reshape(R, C).astype(np.int8), scale
 
 
+def round_fp16(W: np.ndarray):
+    """Nearest IEEE binary16 value (ties to even) of every element, |w| clipped to 65504.
+    Returns (bits uint16, values float64)."""
+    h = np.clip(np.asarray(W, dtype=np.float64), -65504.0, 65504.0).astype(np.float16)
+    return h.view(np.uint16), h.astype(np.float64)
+
+
 def dequantize_rows(q: np.ndarray, scale: np.ndarray) -> np.ndarray:
     return q.astype(np.float64) * np.asarray(scale, dtype=np.float64)[:, None]
 
@@ -58,10 +69,12 @@ def dequantize_groups(q: np.ndarray, scale: np.ndarray, group: int = 64) -> np.n
 
 
 def shadow_matrix(W: np.ndarray, kind: str) -> np.ndarray:
-    """float64 values of the shadow copy of W ('bf16': unchanged, 'int8', 'int4')."""
+    """float64 values of the shadow copy of W ('bf16': unchanged, 'fp16', 'int8', 'int4')."""
     W = np.asarray(W, dtype=np.float64)
     if kind == "bf16":
         return W.copy()
+    if kind == "fp16":
+        return round_fp16(W)[1]
     if kind == "int8":
         return dequantize_rows(*quantize_rows_int8(W))
     if kind == "int4":

@@ -50,10 +50,40 @@ def test_int4_groups():
     assert s[0, 0] == 1.0 and q[0, :5].tolist() == [7, -4, 2, 0, -7]
 
 
+def test_fp16_rounding_hand_worked_values():
+    """Binary16: 10 fraction bits, ties to even, subnormals of 2^-24, largest finite value 65504."""
+    cases = [
+        (1.0, 0x3C00, 1.0),
+        (1.0 + 2.0 ** -11, 0x3C00, 1.0),                       # halfway between 1 and 1 + 2^-10: even fraction
+        (1.0 + 3 * 2.0 ** -11, 0x3C02, 1.0 + 2.0 ** -9),       # halfway between fractions 1 and 2: even is 2
+        (1.0 + 2.0 ** -11 + 2.0 ** -30, 0x3C01, 1.0 + 2.0 ** -10),   # just above a midpoint rounds up
+        (1.0 / 3.0, 0x3555, 0.333251953125),
+        (-0.02, 0xA51F, -0.0200042724609375),
+        (2.0 ** -24, 0x0001, 2.0 ** -24),                      # smallest subnormal
+        (2.0 ** -25, 0x0000, 0.0),                             # halfway to it: ties to even (zero)
+        (3 * 2.0 ** -25, 0x0002, 2.0 ** -23),                  # halfway between subnormals 1 and 2: even
+        (65504.0, 0x7BFF, 65504.0),
+        (1e6, 0x7BFF, 65504.0), (-1e6, 0xFBFF, -65504.0),      # clipped, never infinite
+        (0.0, 0x0000, 0.0),
+    ]
+    W = np.array([[c[0] for c in cases]])
+    bits, vals = S.round_fp16(W)
+    assert bits.dtype == np.uint16
+    for j, (_, b, v) in enumerate(cases):
+        assert bits[0, j] == b and vals[0, j] == v, (j, hex(bits[0, j]), vals[0, j])
+    # relative error bound of a normal value: half a unit in the last place, 2^-11
+    X = rng.normal(0, 0.02, size=4096)
+    X = X[np.abs(X) > 2.0 ** -14]
+    assert (np.abs(S.round_fp16(X)[1] - X) <= np.abs(X) * 2.0 ** -11).all()
+    assert np.array_equal(S.round_fp16(S.round_fp16(X)[1])[1], S.round_fp16(X)[1])    # idempotent
+    assert np.array_equal(S.round_fp16(-X)[1], -S.round_fp16(X)[1])                   # odd
+
+
 def test_shadow_matrix_kinds():
     W = synth.normal(1, 3, 48 * 128, 0.02).reshape(48, 128).astype(np.float64)
     W[5] = 0
     assert np.array_equal(S.shadow_matrix(W, "bf16"), W)
+    assert np.array_equal(S.shadow_matrix(W, "fp16"), S.round_fp16(W)[1])
     q, sc = S.quantize_rows_int8(W)
     assert np.array_equal(S.shadow_matrix(W, "int8"), q.astype(np.float64) * sc[:, None])
     q4, s4 = S.quantize_groups_int4(W)
@@ -83,7 +113,7 @@ def test_oracle_shadow_routing_recall_decreases_with_coarser_quantisation():
     layers = [synth.layer_weights(cfg, l) for l in range(cfg.n_layers)]
     X = synth.tokens(cfg)
     rec = {}
-    for kind in ("bf16", "int8", "int4"):
+    for kind in ("bf16", "fp16", "int8", "int4"):
         sh_layers = _oracle_shadow_layers(cfg, layers, kind)
         c = np.zeros((1, cfg.n_tokens, cfg.n_layers))
         for t in range(cfg.n_tokens):
@@ -92,4 +122,4 @@ def test_oracle_shadow_routing_recall_decreases_with_coarser_quantisation():
             c[0, t] = [O.correct_predictions(idx_s[l], idx_m[l]) for l in range(cfg.n_layers)]
         rec[kind] = O.recall(c, np.ones((1, cfg.n_tokens)), cfg.top_k)
     assert rec["bf16"] == 1.0
-    assert rec["int8"] >= rec["int4"] > cfg.top_k / cfg.n_experts
+    assert rec["fp16"] >= rec["int8"] >= rec["int4"] > cfg.top_k / cfg.n_experts
