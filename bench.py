@@ -342,12 +342,37 @@ def main() -> int:
                 flop_p = 6.0 * c32.hidden * c32.ffn * Tp * c32.top_k
                 pf32 = {"tokens": Tp, "ms": round(ms_p, 3), "TFLOPs": round(flop_p / ms_p / 1e9, 1),
                         "frac_of_fp32_matrix_peak_157.3": round(flop_p / ms_p / 1e9 / 157.3, 3)}
+        # the same fp32 layer with its experts held in binary16 (the paper's FP16 shadow model of
+        # Sections 1, 3.2: half the bytes per token)
+        f16 = None
+        if args.int8_passes > 0:
+            from paper_2512_03927_amd import shadow
+            with shadow.shadow_stack(c32, [layer32], "fp16") as sth:
+                Xh = harness.to_device(X32_np)
+                Yh = torch.empty_like(Xh)
+                for t in range(256):
+                    B.odmoe_decode_step(sth.handle, Xh[t % args.fp32_tokens], Yh[t % args.fp32_tokens], None, None, None)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for t in range(args.fp32_tokens):
+                    B.odmoe_decode_step(sth.handle, Xh[t], Yh[t], None, None, None)
+                torch.cuda.synchronize()
+                elh = time.perf_counter() - t1
+                rh, uh, dh = B.odmoe_time_decode_kernels(sth.handle, 0, Xh, args.fp32_tokens, 2)
+                ubh = c32.top_k * 2 * c32.hidden * c32.ffn * 2
+                f16 = {"workload": c32.name + " with binary16 experts", "tokens_per_s": round(args.fp32_tokens / elh, 1),
+                       "speedup_over_fp32": round(el32 / elh, 3), "bytes_vs_fp32": 0.5,
+                       "ffn_up_us": round(uh, 2), "ffn_up_GBps": round(ubh / uh / 1e3, 1),
+                       "ffn_up_frac_of_hbm_peak": round(ubh / uh / 1e3 / HBM_PEAK_GBPS, 4),
+                       "ffn_down_us": round(dh, 2), "ffn_down_GBps": round(ubh / 2 / dh / 1e3, 1),
+                       "ffn_down_frac_of_hbm_peak": round(ubh / 2 / dh / 1e3 / HBM_PEAK_GBPS, 4)}
+                del Xh, Yh
         ub32 = c32.top_k * 2 * c32.hidden * c32.ffn * 4
         fp32 = {"workload": c32.name, "tokens": args.fp32_tokens,
                 "tokens_per_s": round(args.fp32_tokens / el32, 1),
                 "ffn_up_us": round(u_us, 2), "ffn_up_GBps": round(ub32 / u_us / 1e3, 1),
                 "ffn_down_us": round(d_us, 2), "ffn_down_GBps": round(ub32 / 2 / d_us / 1e3, 1),
-                "route_us": round(r_us, 2), "prefill": pf32}
+                "route_us": round(r_us, 2), "prefill": pf32, "binary16_experts": f16}
         del layer32
         log(f"[bench] fp32: {fp32}")
 
@@ -595,6 +620,19 @@ def main() -> int:
                                                     "main_cacheless": round(main_ms / args.sep_iters, 4)}
         sep["random_prefetch_expectation"] = cs.top_k / cs.n_experts
         del layers_s
+        # the paper's own setting: a full-precision (fp32) stack predicted by its FP16 / INT8 / 4-bit copies
+        cf = cs.small(name="sep-h1024-f2048-e8-k2-16L-fp32", dtype="f32")
+        layers_f = [synth.layer_weights(cf, l) for l in range(cf.n_layers)]
+        xf0 = harness.to_device(synth.tokens(cf)[0])
+        sep["fp32_main"] = {"emulation_workload": cf.name, "mean_recall": {}}
+        with harness.MoEStack(cf, layers_f) as main_f:
+            for kind in ("fp16", "int8", "int4"):
+                with shadow.shadow_stack(cf, layers_f, kind) as sh:
+                    for aligned in (True, False):
+                        r, _, _, _ = shadow.emulate(main_f, sh, xf0, args.sep_iters, aligned)
+                        sep["fp32_main"]["mean_recall"][f"{kind}_{'aligned' if aligned else 'unaligned'}"] = \
+                            round(float(np.mean(r)), 4)
+        del layers_f
         log(f"[bench] sep emulation: {sep}")
 
     # ---- CPU oracle on a bounded sample of the same workload

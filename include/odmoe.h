@@ -36,9 +36,9 @@
  *     bf16 is the upper 16 bits of an fp32 (round-to-nearest-even).
  *   - One expert is ONE contiguous buffer:  W1[F,H] | W3[F,H] | W2[H,F]   (3*H*F elements).
  *   - hidden and ffn must be multiples of 8; 1 <= top_k <= min(n_experts, 8); n_experts <= 1024.
- *   - Experts may instead be int8 codes with a scale per weight row, or packed 4-bit codes with a
- *     scale per group of 64 (odmoe_config.expert_quant): the quantised shadow model of Sections 1
- *     and 3.2, which reads a half resp. 0.28 of the bytes per token.
+ *   - Experts may instead be int8 codes with a scale per weight row, packed 4-bit codes with a
+ *     scale per group of 64, or (fp32 layers) binary16 weights (odmoe_config.expert_quant): the
+ *     quantised shadow model of Sections 1 and 3.2, which reads fewer bytes per token.
  *   - The caller owns every buffer it passes in; weight buffers must outlive the handle.
  *     Streams are borrowed (never destroyed here).  The library owns its slot pool, scratch
  *     buffers, events and, if no copy stream was given, its copy streams.
@@ -81,13 +81,14 @@ typedef enum {
 
 typedef enum { ODMOE_F32 = 0, ODMOE_BF16 = 1 } odmoe_dtype;
 
-/* Weight quantisation of the shadow model (Sections 1, 3.2; the paper names FP16 / INT8 / NF4 and
- * prints no scheme: these are the plain symmetric absmax ones, round half to even).
+/* Weight formats of the shadow model (Sections 1, 3.2; the paper names FP16 / INT8 / NF4 and
+ * prints no scheme: the integer ones are the plain symmetric absmax schemes, round half to even).
  *   INT8_ROW  per weight row:  s = max|w| / 127,  q = clip(rne(w / s), -127, 127)
  *   INT4_G64  per group of 64 consecutive weights of a row:  s = max|w| / 7,  q in -7..7
- * Codes are stored offset-binary in one byte each: q + 128, resp. q + 8.  An all-zero row or
- * group has scale 0 and codes of 0. */
-typedef enum { ODMOE_Q_NONE = 0, ODMOE_Q_INT8_ROW = 1, ODMOE_Q_INT4_G64 = 2 } odmoe_quant;
+ *   F16       every weight rounded to IEEE binary16 (nearest, ties to even, |w| clipped to 65504)
+ * Integer codes are stored offset-binary in one byte each: q + 128, resp. q + 8.  An all-zero row
+ * or group has scale 0 and codes of 0. */
+typedef enum { ODMOE_Q_NONE = 0, ODMOE_Q_INT8_ROW = 1, ODMOE_Q_INT4_G64 = 2, ODMOE_Q_F16 = 3 } odmoe_quant;
 
 #define ODMOE_MAX_TOPK 8
 #define ODMOE_MAX_EXPERTS 1024
@@ -113,7 +114,10 @@ typedef struct {
                           byte j) W1[F][H/2] | W3[F][H/2] | W2[H][F/2], then fp32 scales, one per
                           group of 64 weights of a row, s1[F][H/64] | s3[F][H/64] | s2[H][F/64].
                           hidden and ffn multiples of 64, hidden <= 8192.
-                        Both as odmoe_quantize_expert writes them. */
+                        ODMOE_Q_F16: binary16 weights W1[F,H] | W3[F,H] | W2[H,F]; dtype must be
+                          ODMOE_F32 (the 16-bit shadow of a full-precision model: half its bytes);
+                          hidden <= 8192, ffn <= 32768.
+                        All as odmoe_quantize_expert writes them. */
 } odmoe_config;
 
 typedef struct {
@@ -265,15 +269,17 @@ int odmoe_expert_ffn_static(const odmoe_config* cfg, const void* const* expert_t
 
 /* Bytes of one expert buffer as a handle made from cfg expects it: 3*H*F elements of dtype, or for
  * ODMOE_Q_INT8_ROW 3*H*F code bytes + 4*(2*F + H) bytes of scales, for ODMOE_Q_INT4_G64 3*H*F/2
- * code bytes + 4*(3*H*F/64) bytes of scales.  0 for a NULL or invalid cfg. */
+ * code bytes + 4*(3*H*F/64) bytes of scales, for ODMOE_Q_F16 3*H*F*2.  0 for a NULL or invalid cfg. */
 uint64_t odmoe_expert_bytes(const odmoe_config* cfg);
 
 /*
  * The shadow model's weights (Sections 1, 3.2): quantise w_dev[rows, cols] (row-major, dtype) on
- * the device.  kind: ODMOE_Q_INT8_ROW or ODMOE_Q_INT4_G64 (cols a multiple of 64).  Outputs, each
- * optional (NULL = not wanted), all device pointers:
- *   code_dev     uint8 [rows, cols], offset-binary codes
- *   scale_dev    fp32 [rows] (INT8_ROW) or [rows, cols/64] (INT4_G64): the float64 scale rounded once
+ * the device.  kind: ODMOE_Q_INT8_ROW, ODMOE_Q_INT4_G64 (cols a multiple of 64) or ODMOE_Q_F16.
+ * Outputs, each optional (NULL = not wanted), all device pointers:
+ *   code_dev     uint8 [rows, cols], offset-binary codes; F16: rows*cols binary16 values (two
+ *                bytes each, 2-byte aligned)
+ *   scale_dev    fp32 [rows] (INT8_ROW) or [rows, cols/64] (INT4_G64): the float64 scale rounded
+ *                once; F16 has none (must be NULL)
  *   dequant_dev  [rows, cols] in dtype: q * scale (float64) rounded once to dtype -- the weights a
  *                shadow copy held in the storage dtype uses
  * The scale, the division and the rounding are done in float64, so every code equals the one a
@@ -283,7 +289,7 @@ int odmoe_quantize(const void* w_dev, int32_t dtype, int64_t rows, int64_t cols,
                    uint8_t* code_dev, float* scale_dev, void* dequant_dev, void* stream);
 
 /* One stored expert W1[F,H] | W3[F,H] | W2[H,F] (cfg->dtype, device) into the expert buffer of
- * format `kind` (ODMOE_Q_INT8_ROW or ODMOE_Q_INT4_G64) described at odmoe_config; dst_dev: device,
+ * format `kind` (ODMOE_Q_INT8_ROW, ODMOE_Q_INT4_G64 or ODMOE_Q_F16) described at odmoe_config; dst_dev: device,
  * odmoe_expert_bytes of the config with expert_quant = kind.  The codes and scales are those of
  * odmoe_quantize on the three matrices.  cfg->expert_quant is ignored.  Asynchronous on `stream`. */
 int odmoe_quantize_expert(const odmoe_config* cfg, int32_t kind, const void* expert_dev, void* dst_dev,

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libodmoe.so")
 
 ODMOE_OK, ODMOE_EINVAL, ODMOE_ENOMEM, ODMOE_EHIP, ODMOE_ESTATE, ODMOE_EBUSY = 0, -1, -2, -3, -4, -5
 ODMOE_F32, ODMOE_BF16 = 0, 1
-ODMOE_Q_NONE, ODMOE_Q_INT8_ROW, ODMOE_Q_INT4_G64 = 0, 1, 2
+ODMOE_Q_NONE, ODMOE_Q_INT8_ROW, ODMOE_Q_INT4_G64, ODMOE_Q_F16 = 0, 1, 2, 3
 ODMOE_MAX_TOPK = 8
 ODMOE_MAX_EXPERTS = 1024
 

@@ -14,7 +14,7 @@ LIB = os.path.join(PKG, "libodmoe.so")
 HOSTSIM = os.path.join(PKG, "libodmoe_hostsim.so")
 C_DEMO = os.path.join(PKG, "c_abi_demo")   # plain C program on top of the C ABI (run by a GPU test)
 
-HIP_SOURCES = ["odmoe_api.hip", "decode_kernels.hip", "quant_kernels.hip", "quant4_kernels.hip", "prefill_kernels.hip"]
+HIP_SOURCES = ["odmoe_api.hip", "decode_kernels.hip", "quant_kernels.hip", "quant4_kernels.hip", "f16_kernels.hip", "prefill_kernels.hip"]
 HIP_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 VALU forms have produced wrong results on these machines: keep them off

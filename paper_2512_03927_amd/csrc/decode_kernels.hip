@@ -780,6 +780,7 @@ hipError_t launch_ffn_up(hipStream_t s, const Shape& sh, const ExpertSrc& src, c
                          const void* x, float* hbuf) {
   if (sh.quant == ODMOE_Q_INT8_ROW) return launch_ffn_up_q8(s, sh, src, idx, x, hbuf);
   if (sh.quant == ODMOE_Q_INT4_G64) return launch_ffn_up_q4(s, sh, src, idx, x, hbuf);
+  if (sh.quant == ODMOE_Q_F16) return launch_ffn_up_f16(s, sh, src, idx, x, hbuf);
   const int vec = sh.dtype == ODMOE_F32 ? 4 : 8;
   const int nch = (sh.H + WAVE * vec - 1) / (WAVE * vec);
   if (nch <= 16) {
@@ -805,6 +806,7 @@ hipError_t launch_ffn_down(hipStream_t s, const Shape& sh, const ExpertSrc& src,
                            const int32_t* idx, const float* gate, const float* hbuf, void* y) {
   if (sh.quant == ODMOE_Q_INT8_ROW) return launch_ffn_down_q8(s, sh, src, idx, gate, hbuf, y);
   if (sh.quant == ODMOE_Q_INT4_G64) return launch_ffn_down_q4(s, sh, src, idx, gate, hbuf, y);
+  if (sh.quant == ODMOE_Q_F16) return launch_ffn_down_f16(s, sh, src, idx, gate, hbuf, y);
   const int vec = sh.dtype == ODMOE_F32 ? 4 : 8;
   const int nc = (sh.F + WAVE * vec - 1) / (WAVE * vec);
   int cpw = 0, nwb = 0;

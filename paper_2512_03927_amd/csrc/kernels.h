@@ -30,7 +30,7 @@ struct Shape {
   int32_t host_link = 0;
   // odmoe_quant of the expert buffers: 0 = weights in `dtype`; ODMOE_Q_INT8_ROW = int8 codes with
   // one fp32 scale per weight row; ODMOE_Q_INT4_G64 = packed 4-bit codes with one fp32 scale per
-  // group of 64 (x, y and the router stay in `dtype`).
+  // group of 64; ODMOE_Q_F16 = binary16 weights (x, y and the router stay in `dtype`).
   int32_t quant = 0;
 };
 
@@ -87,6 +87,17 @@ hipError_t launch_ffn_down_q4(hipStream_t s, const Shape& sh, const ExpertSrc& s
 // [rows, cols/64]: the codes of launch_quantize(ODMOE_Q_INT4_G64), two per byte.
 hipError_t launch_quantize_pack4(hipStream_t s, const void* w, int32_t dtype, int64_t rows, int64_t cols,
                                  uint8_t* packed, float* scale);
+
+// ... and over binary16 expert buffers W1 | W3 | W2 (layers of dtype fp32 only: x, h, y fp32);
+// sh.quant == ODMOE_Q_F16.
+bool f16_supported(const Shape& sh);   // fp32 layer, H and F multiples of 8, H <= 8192, F <= 32768
+hipError_t launch_ffn_up_f16(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                             const void* x, float* hbuf);
+hipError_t launch_ffn_down_f16(hipStream_t s, const Shape& sh, const ExpertSrc& src, const int32_t* idx,
+                               const float* gate, const float* hbuf, void* y);
+// w[n] (dtype) -> binary16 bits (nearest, ties to even, clipped to the largest finite value) in
+// code, and the value they stand for rounded to dtype in deq; either may be null.
+hipError_t launch_round_f16(hipStream_t s, const void* w, int32_t dtype, size_t n, uint16_t* code, void* deq);
 
 // Symmetric absmax quantisation of w[rows, cols] (dtype) on the device; kind is an odmoe_quant.
 // code (u8, offset-binary), scale (fp32, per row or per group of 64) and deq (code * scale rounded

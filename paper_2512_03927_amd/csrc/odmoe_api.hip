@@ -58,6 +58,7 @@ size_t expert_bytes_of(const odmoe_config& c) {
   const size_t hf = (size_t)c.hidden * c.ffn;
   if (c.expert_quant == ODMOE_Q_INT8_ROW) return 3 * hf + sizeof(float) * (2 * (size_t)c.ffn + c.hidden);
   if (c.expert_quant == ODMOE_Q_INT4_G64) return 3 * hf / 2 + sizeof(float) * (3 * hf / 64);
+  if (c.expert_quant == ODMOE_Q_F16) return 3 * hf * 2;
   return 3 * hf * dtype_size(c.dtype);
 }
 
@@ -122,9 +123,16 @@ int validate_cfg(const odmoe_config* c) {
     return fail(ODMOE_EINVAL, "n_slots %d must be 0 (resident) or >= top_k", c->n_slots);
   if (c->dtype != ODMOE_F32 && c->dtype != ODMOE_BF16) return fail(ODMOE_EINVAL, "bad dtype %d", c->dtype);
   if (c->glue != 0 && c->glue != 1) return fail(ODMOE_EINVAL, "bad glue %d", c->glue);
-  if (c->expert_quant != ODMOE_Q_NONE && c->expert_quant != ODMOE_Q_INT8_ROW && c->expert_quant != ODMOE_Q_INT4_G64)
-    return fail(ODMOE_EINVAL, "expert_quant %d: experts are stored in dtype (0), as int8 rows (1) or 4-bit groups (2)",
+  if (c->expert_quant < ODMOE_Q_NONE || c->expert_quant > ODMOE_Q_F16)
+    return fail(ODMOE_EINVAL,
+                "expert_quant %d: experts are stored in dtype (0), as int8 rows (1), 4-bit groups (2) or binary16 (3)",
                 c->expert_quant);
+  if (c->expert_quant == ODMOE_Q_F16) {
+    Shape sh{c->hidden, c->ffn, c->n_experts, c->top_k, c->dtype};
+    if (!f16_supported(sh))
+      return fail(ODMOE_EINVAL, "binary16 experts need dtype fp32, hidden (%d) <= 8192 and ffn (%d) <= 32768",
+                  c->hidden, c->ffn);
+  }
   if (c->expert_quant == ODMOE_Q_INT4_G64 && (c->hidden % 64 || c->ffn % 64 || c->hidden > 8192))
     return fail(ODMOE_EINVAL, "4-bit experts need hidden (%d) and ffn (%d) to be multiples of 64 and hidden <= 8192",
                 c->hidden, c->ffn);
@@ -275,9 +283,17 @@ int odmoe_quantize(const void* w_dev, int32_t dtype, int64_t rows, int64_t cols,
   if (!w_dev) return fail(ODMOE_EINVAL, "w is NULL");
   if (dtype != ODMOE_F32 && dtype != ODMOE_BF16) return fail(ODMOE_EINVAL, "bad dtype %d", dtype);
   if (rows < 0 || cols < 0) return fail(ODMOE_EINVAL, "rows / cols negative");
-  if (kind != ODMOE_Q_INT8_ROW && kind != ODMOE_Q_INT4_G64) return fail(ODMOE_EINVAL, "bad quantisation kind %d", kind);
+  if (kind != ODMOE_Q_INT8_ROW && kind != ODMOE_Q_INT4_G64 && kind != ODMOE_Q_F16)
+    return fail(ODMOE_EINVAL, "bad quantisation kind %d", kind);
   if (kind == ODMOE_Q_INT4_G64 && cols % 64) return fail(ODMOE_EINVAL, "cols (%lld) must be a multiple of 64", (long long)cols);
   if (rows > 0x7fffffffLL) return fail(ODMOE_EINVAL, "too many rows");
+  if (kind == ODMOE_Q_F16) {
+    if (scale_dev) return fail(ODMOE_EINVAL, "binary16 weights have no scales: scale_dev must be NULL");
+    if (reinterpret_cast<uintptr_t>(code_dev) & 1u) return fail(ODMOE_EINVAL, "code_dev must be 2-byte aligned");
+    HIP_TRY(launch_round_f16(static_cast<hipStream_t>(stream), w_dev, dtype, (size_t)rows * (size_t)cols,
+                             reinterpret_cast<uint16_t*>(code_dev), dequant_dev));
+    return ODMOE_OK;
+  }
   HIP_TRY(launch_quantize(static_cast<hipStream_t>(stream), w_dev, dtype, rows, cols, kind, code_dev, scale_dev,
                           dequant_dev));
   return ODMOE_OK;
@@ -286,7 +302,8 @@ int odmoe_quantize(const void* w_dev, int32_t dtype, int64_t rows, int64_t cols,
 int odmoe_quantize_expert(const odmoe_config* cfg, int32_t kind, const void* expert_dev, void* dst_dev,
                           void* stream) {
   if (!cfg) return fail(ODMOE_EINVAL, "cfg is NULL");
-  if (kind != ODMOE_Q_INT8_ROW && kind != ODMOE_Q_INT4_G64) return fail(ODMOE_EINVAL, "bad quantisation kind %d", kind);
+  if (kind != ODMOE_Q_INT8_ROW && kind != ODMOE_Q_INT4_G64 && kind != ODMOE_Q_F16)
+    return fail(ODMOE_EINVAL, "bad quantisation kind %d", kind);
   odmoe_config qc = *cfg;
   qc.expert_quant = kind;
   int rc = validate_cfg(&qc);
@@ -302,6 +319,8 @@ int odmoe_quantize_expert(const odmoe_config* cfg, int32_t kind, const void* exp
     HIP_TRY(launch_quantize(s, src, dt, F, H, kind, code, scale, nullptr));                             // W1
     HIP_TRY(launch_quantize(s, src + hf * es, dt, F, H, kind, code + hf, scale + F, nullptr));          // W3
     HIP_TRY(launch_quantize(s, src + 2 * hf * es, dt, H, F, kind, code + 2 * hf, scale + 2 * F, nullptr));  // W2
+  } else if (kind == ODMOE_Q_F16) {
+    HIP_TRY(launch_round_f16(s, src, dt, 3 * hf, reinterpret_cast<uint16_t*>(dst_dev), nullptr));
   } else {
     float* scale = reinterpret_cast<float*>(code + 3 * hf / 2);
     const size_t ng = hf / 64;   // groups (= scales) per matrix

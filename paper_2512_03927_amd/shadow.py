@@ -6,12 +6,14 @@ stack on the same GPU, built from the full stack's stored weights by the library
 (`odmoe_quantize`, `odmoe_quantize_expert`):
 
   'bf16'  an identical copy (the predictor that is always right)
+  'fp16'  fp32 stacks only: experts rounded to IEEE binary16, read by the binary16 GEMV kernels
+          (half the bytes per token): the paper's FP16 shadow of its FP32 model
   'int8'  experts as int8 codes with a scale per weight row, read by the int8 GEMV kernels (half
           the bytes per token)
   'int4'  experts as packed 4-bit codes with a scale per group of 64 weights, read by the 4-bit
           GEMV kernels (0.28 of the bytes per token)
 
-In both quantised copies the router is quantised the same way and held dequantised in the storage
+In every quantised copy the router is quantised the same way and held dequantised in the storage
 dtype (it is tiny).  This module only moves buffers and calls the library (marshalling);
 `emulate` is `odmoe_sep_emulate`.
 """
@@ -24,7 +26,7 @@ import torch
 from . import binding as B
 from . import harness, synth
 
-QUANT_OF_KIND = {"int8": B.ODMOE_Q_INT8_ROW, "int4": B.ODMOE_Q_INT4_G64}
+QUANT_OF_KIND = {"int8": B.ODMOE_Q_INT8_ROW, "int4": B.ODMOE_Q_INT4_G64, "fp16": B.ODMOE_Q_F16}
 
 
 def _dtype_code(cfg: synth.MoEConfig) -> int:
@@ -34,7 +36,7 @@ def _dtype_code(cfg: synth.MoEConfig) -> int:
 def shadow_stack(cfg: synth.MoEConfig, layers: Sequence, kind: str, device: str = "cuda:0") -> harness.MoEStack:
     """A resident stack of cfg's shape whose weights are the `kind` copy of `layers` (stored
     per-layer (Wg, b, experts) as synth makes them)."""
-    if kind not in ("bf16", "int8", "int4"):
+    if kind not in ("bf16", "fp16", "int8", "int4"):
         raise ValueError(kind)
     rcfg = cfg.small(n_slots=0)
     if kind == "bf16":

@@ -67,7 +67,14 @@ def test_argument_errors_need_no_gpu():
     assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 + 4 * (2 * 14336 + 4096)
     c.expert_quant = B.ODMOE_Q_INT4_G64
     assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 // 2 + 4 * (3 * 4096 * 14336 // 64)
+    c.expert_quant = B.ODMOE_Q_F16                     # binary16 experts: fp32 layers only
+    assert B.odmoe_expert_bytes(c) == 0 and "fp32" in B.odmoe_last_error()
+    c.dtype = B.ODMOE_F32
+    assert B.odmoe_expert_bytes(c) == 3 * 4096 * 14336 * 2
+    c.expert_quant = 4
+    assert B.odmoe_expert_bytes(c) == 0
     assert B.odmoe_expert_bytes(bad) == 0
+    assert lib.odmoe_quantize(1, 0, 4, 64, 3, None, 1, None, None) == B.ODMOE_EINVAL        # binary16 has no scales
     assert lib.odmoe_quantize(None, 1, 4, 64, 1, None, None, None, None) == B.ODMOE_EINVAL
     assert lib.odmoe_quantize(1, 1, 4, 100, 2, None, None, None, None) == B.ODMOE_EINVAL     # 4-bit groups of 64
     assert lib.odmoe_quantize(1, 1, 4, 64, 7, None, None, None, None) == B.ODMOE_EINVAL

@@ -95,7 +95,9 @@ def _oracle_quant_layer(cfg, layer, kind="int8"):
     for flat in experts:
         parts = []
         for W in O.split_expert(flat, Hd, F):
-            if kind == "int8":
+            if kind == "fp16":
+                parts.append(S.round_fp16(O.widen(W))[1])
+            elif kind == "int8":
                 q, s = S.quantize_rows_int8(O.widen(W))
                 parts.append(S.dequantize_rows(q, s.astype(np.float32)))
             else:
@@ -140,6 +142,67 @@ def test_packed_4bit_expert_buffer_is_bit_exact(H, dtype):
         assert np.array_equal(scales[s_off:s_off + rows * cols // 64].reshape(rows, cols // 64), s.astype(np.float32))
         c_off += rows * cols // 2
         s_off += rows * cols // 64
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_device_rounding_to_binary16_is_bit_exact(H, dtype):
+    import torch
+    from paper_2512_03927_amd import binding as B
+    rows, cols = 37, 200
+    W = synth.normal(4, 9, rows * cols, 1.0).reshape(rows, cols)
+    W[0, :12] = [1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 2.0 ** -24, 2.0 ** -25, 3 * 2.0 ** -25, 65504, 1e6, -1e6, 0.0, -0.02,
+                 1 / 3, 6.1e-5]                                    # ties, subnormals, clipping
+    W[1] *= 1e-5                                                   # a row in binary16's subnormal range
+    W = synth.store(W.astype(np.float32), dtype)
+    w = H.to_device(W)
+    code = torch.zeros((rows, cols), dtype=torch.int16, device="cuda:0")
+    deq = torch.zeros_like(w)
+    B.odmoe_quantize(w, B.ODMOE_F32 if dtype == "f32" else B.ODMOE_BF16, rows, cols, B.ODMOE_Q_F16, code, None, deq,
+                     torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    bits, vals = S.round_fp16(O.widen(W))
+    assert np.array_equal(code.cpu().numpy().view(np.uint16), bits)
+    assert np.array_equal(H.from_device(deq), O.round_to_storage(vals, dtype))
+
+
+F16_SHAPES = [
+    (520, 1048, 8, 2),         # ragged: a chunk of 512 weights plus 8
+    (2048, 1408, 8, 6),        # the fine-grained layer shape (config 5), k = 6
+    (8, 8, 2, 1),              # the smallest shape
+    (4608, 40, 3, 2),          # nine register chunks in the w1/w3 GEMV
+    (64, 32768, 2, 2),         # the longest ffn vector binary16 experts take
+    (4096, 14336, 3, 2),       # the Mixtral layer shape in the paper's full precision
+]
+
+
+@pytest.mark.parametrize("Hd,F,E,k", F16_SHAPES)
+def test_binary16_expert_layer_matches_oracle_on_rounded_weights(H, Hd, F, E, k):
+    """fp32 layer whose experts are held in binary16: routing bit-exact, outputs within the fp32
+    tolerance of the layer definition evaluated by the oracle on the rounded weights."""
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", Hd, F, E, k, dtype="f32", n_tokens=2, seed=77)
+    layer = synth.layer_weights(cfg)
+    X = synth.tokens(cfg)
+    Wg_s, b, ex_s = _oracle_quant_layer(cfg, layer, "fp16")
+    with shadow.shadow_stack(cfg, [layer], "fp16") as st:
+        assert st.expert_bytes == 3 * Hd * F * 2
+        x = H.to_device(X)
+        idx, gate = st.route(0, x)
+        yn = H.from_device(st.ffn(0, idx, gate, x))
+        for t in range(cfg.n_tokens):
+            y_ref, idx_ref, g_ref = O.moe_layer(X[t], Wg_s, b, ex_s, k)
+            assert np.array_equal(idx.cpu().numpy()[t], idx_ref)
+            assert np.max(np.abs(gate.cpu().numpy()[t].astype(np.float64) - g_ref)) <= 1e-6
+            assert np.max(np.abs(O.widen(yn[t]) - y_ref)) <= 1e-4
+            yt, idx_t, _ = st.decode(x[t])
+            assert np.array_equal(H.from_device(yt), yn[t]) and np.array_equal(idx_t[0], idx_ref)
+
+
+def test_binary16_experts_are_refused_for_bf16_layers(H):
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", 64, 64, 4, 2, dtype="bf16", n_tokens=1, seed=3)
+    with pytest.raises(ValueError):
+        shadow.shadow_stack(cfg, [synth.layer_weights(cfg)], "fp16")
 
 
 Q4_SHAPES = [
@@ -257,13 +320,14 @@ def test_4bit_expert_layer_random_small_shapes(H, Hd, F, E, k, dtype):
     _check_random_quant_shape(H, "int4", Hd, F, E, k, dtype)
 
 
-@pytest.mark.parametrize("kind,byte_share", [("int8", 0.51), ("int4", 0.29)])
+@pytest.mark.parametrize("kind,byte_share", [("int8", 0.51), ("int4", 0.29), ("fp16", 0.5001)])
 def test_quantised_stack_cacheless_and_resident_agree_and_move_fewer_bytes(H, kind, byte_share):
     """Quantised experts through the slot pool: the same bits as resident, and each load is the
     quantised expert's size (int8: half of bf16 plus the row scales; 4-bit: 0.281 of bf16)."""
     import torch
     from paper_2512_03927_amd import shadow
-    cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=5, n_slots=4, dtype="bf16", n_tokens=2, glue=1, seed=63)
+    dtype = "f32" if kind == "fp16" else "bf16"
+    cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=5, n_slots=4, dtype=dtype, n_tokens=2, glue=1, seed=63)
     layers = [synth.layer_weights(cfg, l) for l in range(cfg.n_layers)]
     X = synth.tokens(cfg)
     with shadow.shadow_stack(cfg, layers, kind) as res:
@@ -279,13 +343,14 @@ def test_quantised_stack_cacheless_and_resident_agree_and_move_fewer_bytes(H, ki
                 y_c, idx_c, s = st.decode(x)
                 assert np.array_equal(idx_c, idx_r) and np.array_equal(H.from_device(y_c), H.from_device(y_r))
                 assert s.loads == cfg.n_layers * cfg.top_k and s.h2d_bytes == s.loads * st.expert_bytes
-                x_ref, IDX, _ = O.stack_decode(X[t], layers_o, cfg.top_k, "bf16", glue=1)
+                x_ref, IDX, _ = O.stack_decode(X[t], layers_o, cfg.top_k, dtype, glue=1)
                 assert np.array_equal(idx_c, IDX)
                 ref = O.widen(x_ref)
-                assert np.max(np.abs(O.widen(H.from_device(y_c)) - ref)) <= BF16_REL * np.max(np.abs(ref))
+                tol = 1e-4 if dtype == "f32" else BF16_REL * np.max(np.abs(ref))
+                assert np.max(np.abs(O.widen(H.from_device(y_c)) - ref)) <= tol
 
 
-@pytest.mark.parametrize("kind,Hd,F", [("int8", 528, 1040), ("int4", 576, 1088)])
+@pytest.mark.parametrize("kind,Hd,F", [("int8", 528, 1040), ("int4", 576, 1088), ("fp16", 520, 1048)])
 def test_quantised_experts_in_place_from_host_memory_and_through_the_static_entry_point(H, kind, Hd, F):
     """The quantised expert formats on the other routes into the same kernels: read in place from
     pinned host memory (n_slots = 0, host pointers) and through odmoe_expert_ffn_static; both give
@@ -293,7 +358,8 @@ def test_quantised_experts_in_place_from_host_memory_and_through_the_static_entr
     import torch
     from paper_2512_03927_amd import binding as B
     from paper_2512_03927_amd import shadow
-    cfg = synth.MoEConfig("t", Hd, F, 8, 2, dtype="bf16", n_tokens=3, seed=65)
+    dtype = "f32" if kind == "fp16" else "bf16"
+    cfg = synth.MoEConfig("t", Hd, F, 8, 2, dtype=dtype, n_tokens=3, seed=65)
     layer = synth.layer_weights(cfg)
     X = synth.tokens(cfg)
     with shadow.shadow_stack(cfg, [layer], kind) as res:
@@ -307,20 +373,21 @@ def test_quantised_experts_in_place_from_host_memory_and_through_the_static_entr
             y_host = H.from_device(host.ffn(0, idx, gate, x))
             assert np.array_equal(y_host, y_res)
         table = torch.tensor([e.data_ptr() for e in experts[0]], dtype=torch.int64, device="cuda:0")
-        c = B.odmoe_config(cfg.hidden, cfg.ffn, cfg.n_experts, cfg.top_k, 1, 0, B.ODMOE_BF16, 0,
-                           shadow.QUANT_OF_KIND[kind])
+        c = B.odmoe_config(cfg.hidden, cfg.ffn, cfg.n_experts, cfg.top_k, 1, 0,
+                           B.ODMOE_F32 if dtype == "f32" else B.ODMOE_BF16, 0, shadow.QUANT_OF_KIND[kind])
         y_static = torch.zeros_like(x)
         B.odmoe_expert_ffn_static(c, table, idx, gate, x, cfg.n_tokens, y_static, torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
         assert np.array_equal(H.from_device(y_static), y_res)
 
 
-@pytest.mark.parametrize("kind", ["int8", "int4"])
+@pytest.mark.parametrize("kind", ["int8", "int4", "fp16"])
 def test_quantised_experts_skip_an_idx_that_is_no_expert_id(H, kind):
     """As for experts stored in dtype: an idx entry outside [0, E) is never used as a table index,
     and that rank adds nothing to y."""
     from paper_2512_03927_amd import shadow
-    cfg = synth.MoEConfig("t", 320, 576, 6, 3, dtype="bf16", n_tokens=2, seed=69)
+    dtype = "f32" if kind == "fp16" else "bf16"
+    cfg = synth.MoEConfig("t", 320, 576, 6, 3, dtype=dtype, n_tokens=2, seed=69)
     layer = synth.layer_weights(cfg)
     X = synth.tokens(cfg)
     _, _, ex_s = _oracle_quant_layer(cfg, layer, kind)
@@ -337,7 +404,8 @@ def test_quantised_experts_skip_an_idx_that_is_no_expert_id(H, kind):
             for i in range(cfg.top_k):
                 if i != skip:
                     ref += g[t, i] * O.expert_ffn(*ex_s[ids[t, i]], X[t])
-            assert np.max(np.abs(O.widen(yb[t]) - ref)) <= ONE_BF16_ROUNDING * np.max(np.abs(ref))
+            assert np.max(np.abs(O.widen(yb[t]) - ref)) <= (1e-4 if dtype == "f32" else
+                                                             ONE_BF16_ROUNDING * np.max(np.abs(ref)))
 
 
 def test_sep_emulate_refuses_stacks_that_do_not_match(H):
@@ -400,3 +468,32 @@ def test_shadow_stack_hints(H):
     late = slice(n_iter // 2, None)
     assert np.mean(rec[("int4", False)][late]) < np.mean(rec[("int4", True)][late])
     assert rec[("int4", False)][0] == rec[("int4", True)][0]          # first iteration starts aligned
+
+
+def test_shadow_copies_of_a_full_precision_stack(H):
+    """The paper's setting (Section 3.2): an FP32 model predicted by its FP16 / INT8 / 4-bit copies.
+    Hints never change the FP32 stack's output; a milder quantisation predicts no worse; aligned
+    beats unaligned late in the chain."""
+    from paper_2512_03927_amd import shadow
+    cfg = synth.MoEConfig("t", 256, 512, 8, 2, n_layers=8, n_slots=4, dtype="f32", n_tokens=1, glue=1, seed=43)
+    layers = [synth.layer_weights(cfg, l) for l in range(cfg.n_layers)]
+    x0 = H.to_device(synth.tokens(cfg)[0])
+    n_iter = 24
+    with H.MoEStack(cfg, layers) as main:
+        x = x0
+        for _ in range(n_iter):
+            x, _, _ = main.decode(x)
+        x_last = H.from_device(x).copy()
+        rec = {}
+        for kind in ("fp16", "int8", "int4"):
+            with shadow.shadow_stack(cfg, layers, kind) as sh:
+                for aligned in (True, False):
+                    r, x_end, _, _ = shadow.emulate(main, sh, x0, n_iter, aligned)
+                    rec[(kind, aligned)] = r
+                    assert np.array_equal(H.from_device(x_end), x_last)
+    m = {key: float(np.mean(v)) for key, v in rec.items()}
+    print("mean recall, fp32 main:", {f"{k_}-{a}": round(v, 3) for (k_, a), v in m.items()})
+    assert m[("fp16", True)] >= m[("int8", True)] >= m[("int4", True)] > cfg.top_k / cfg.n_experts
+    assert m[("fp16", True)] > 0.95
+    late = slice(n_iter // 2, None)
+    assert np.mean(rec[("int4", False)][late]) < np.mean(rec[("int4", True)][late])
