@@ -472,6 +472,23 @@ def main() -> int:
                 B.odmoe_decode_step(sth.handle, xs[t % len(xs)], yh, None, None, None)
             torch.cuda.synchronize()
             inplace_ms = (time.perf_counter() - t2) / n_inp * 1e3
+        # the paper's predictor at this scale (Sections 1, 3.2): an int8 copy of the stack, resident in
+        # HBM, decodes each token first; its routing is the prediction the cacheless stack starts its
+        # copies from (the copy restarts from the full stack's input every iteration)
+        shadow_pred = None
+        if args.sep_iters > 0:
+            from paper_2512_03927_amd import shadow
+            t2 = time.time()
+            with shadow.shadow_stack(c, layers_u, "int8") as shq:
+                n_it = max(4, n_tok // 4)
+                shadow.emulate(stc, shq, xs[0], 2, True)                  # warm-up
+                rec, _, sh_ms, main_ms = shadow.emulate(stc, shq, xs[0], n_it, True)
+                shadow_pred = {"shadow": "int8 experts, resident in HBM", "iterations": n_it,
+                               "recall": round(float(np.mean(rec)), 4),
+                               "shadow_ms_per_token": round(sh_ms / n_it, 3),
+                               "main_ms_per_token": round(main_ms / n_it, 3),
+                               "shadow_hbm_GB": round(len(layers_u) * c.n_experts * shq.expert_bytes / 1e9, 2)}
+            log(f"[bench] {c.name}: int8 shadow predictor {shadow_pred} ({time.time() - t2:.1f} s)")
         step_ms = el / n_tok * 1e3
         # load-window check of the paper (Section 3.1): per layer, t^M = router + glue (the stand-in
         # for the main node's work), t^W = expert FFN, against the time to load one layer's k experts
@@ -498,7 +515,7 @@ def main() -> int:
                                          "link_GBps": round(c.n_layers * c.top_k * c.expert_bytes / inplace_ms / 1e6, 2),
                                          "over_copy_only": round(inplace_ms / load_ms, 4),
                                          "hbm_expert_bytes": 0, "same_output_bits_as_slot_pool": same_bits},
-               "by_hint_miss_rate": by_recall,
+               "by_hint_miss_rate": by_recall, "with_int8_shadow_predictor": shadow_pred,
                "load_window": {"n_groups": n_groups, "t_M_ms": round(t_m, 4), "t_W_ms": round(t_w, 4),
                                "t_maxload_ms": round(window, 4), "t_load_per_layer_ms": round(t_load_layer, 4),
                                "io_bottlenecked": bool(t_load_layer > window)},
