@@ -170,6 +170,7 @@ F16_SHAPES = [
     (2048, 1408, 8, 6),        # the fine-grained layer shape (config 5), k = 6
     (8, 8, 2, 1),              # the smallest shape
     (4608, 40, 3, 2),          # nine register chunks in the w1/w3 GEMV
+    (8192, 64, 2, 2),          # sixteen: the widest hidden vector binary16 experts take
     (64, 32768, 2, 2),         # the longest ffn vector binary16 experts take
     (4096, 14336, 3, 2),       # the Mixtral layer shape in the paper's full precision
 ]
